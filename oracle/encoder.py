@@ -1,0 +1,176 @@
+"""CPU reference for the vision encoder and the merge/projector
+(TEST INFRASTRUCTURE ONLY).
+
+The paper's "vision encoding" stage (Sec. 2.1, Fig. 1) turns preprocessed
+patches into embeddings "in a unified format" for the LLM; the encoders it
+serves are ViT variants (Table 1).  The paper gives no arithmetic, so this file
+is the textbook pre-LN ViT written out, evaluated in one floating-point type
+(`dtype`, default float64) with no intermediate rounding:
+
+  embed     X = patches @ W_pe.T + b_pe ; optional CLS row first in each
+            segment ; position term added per row
+  block     x = x + Attn(LN1(x)) @ W_o.T + b_o
+            x = x + GELU(LN2(x) @ W_1.T + b_1) @ W_2.T + b_2        (x L)
+  LN        (x - mean)/sqrt(var + eps) * gamma + beta, biased variance over d
+  Attn      [q|k|v] = h @ W_qkv.T + b_qkv, head j = columns [j*dh, (j+1)*dh) of
+            each third; softmax(q k^T / sqrt(dh)) v over the keys of the SAME
+            segment (request) only, all keys visible (bidirectional)
+  GELU      x/2 * (1 + erf(x/sqrt 2))
+  final LN  optional
+  merge     LN_m(x); each group of merge^2 consecutive rows is concatenated
+            into one row of width merge^2*d; out = GELU(Y @ W_m1.T + b_m1) @ W_m2.T + b_m2
+
+Library primitives used as steps: numpy matmul, scipy.special.erf.  Attention
+is evaluated in blocks of query rows only to bound memory; every row still
+gets a full-row, max-subtracted softmax.
+
+Pins (tests/test_oracle_encoder.py): softmax rows sum to 1; single-key segment
+returns V; zero queries return mean(V); agreement with a pure-Python triple
+loop (oracle/naive.py); permutation equivariance without position terms;
+segment independence; LN output statistics; GELU identities and tabulated erf
+values; L=0 reduces to one library GEMM; zeroed W_o / W_2 make blocks the
+identity; merge view against a brute-force gather.  There are no published
+output values for any encoder in the paper: beyond these pins the encoder
+output rests on "oracle == definition" (parity unpinned against the outside
+world).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence
+
+import numpy as np
+from scipy.special import erf
+
+from .preprocess import token_coords, token_grid
+
+
+def layernorm(x, gamma, beta, eps):
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def softmax_rows(s):
+    s = s - s.max(axis=-1, keepdims=True)
+    p = np.exp(s)
+    return p / p.sum(axis=-1, keepdims=True)
+
+
+def attention(q, k, v, cu_seqlens: Sequence[int], heads: int, q_block: int = 1024,
+              return_probs: bool = False):
+    """q, k, v: [T, d].  Block-diagonal bidirectional attention: rows
+    cu_seqlens[i]:cu_seqlens[i+1] form segment i."""
+    T, d = q.shape
+    dh = d // heads
+    scale = 1.0 / np.sqrt(dh)
+    out = np.zeros_like(q)
+    probs = []
+    for s in range(len(cu_seqlens) - 1):
+        a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if b == a:
+            continue
+        for h in range(heads):
+            c = slice(h * dh, (h + 1) * dh)
+            kk, vv = k[a:b, c], v[a:b, c]
+            for r in range(a, b, q_block):
+                r1 = min(b, r + q_block)
+                p = softmax_rows((q[r:r1, c] @ kk.T) * scale)
+                out[r:r1, c] = p @ vv
+                if return_probs:
+                    probs.append(p)
+    return (out, probs) if return_probs else out
+
+
+def position_rows(desc, items_grids, weights, dtype):
+    """Position term for every hidden row (incl. CLS rows), in row order."""
+    chunks = []
+    for (gt, gh, gw) in items_grids:
+        n = gt * gh * gw
+        if n == 0:
+            continue
+        rows = n + (1 if desc.use_cls else 0)
+        if desc.pos == "learned1d":
+            chunks.append(weights["pos0"][:rows].astype(dtype))
+        elif desc.pos == "sep2d":
+            co = token_coords(gt, gh, gw, desc.merge)
+            pr = weights["pos0"][co[:, 1]].astype(dtype) + weights["pos1"][co[:, 2]].astype(dtype)
+            if desc.use_cls:
+                pr = np.concatenate([np.zeros((1, desc.d), dtype), pr], 0)
+            chunks.append(pr)
+        else:
+            chunks.append(np.zeros((rows, desc.d), dtype))
+    if not chunks:
+        return np.zeros((0, desc.d), dtype)
+    return np.concatenate(chunks, 0)
+
+
+def grids_of(items, desc):
+    return [token_grid(it.modality, it.n_frames, it.dst_h, it.dst_w, desc.patch, desc.tpatch, desc.merge)
+            for it in items]
+
+
+def cu_seqlens_of(grids, use_cls) -> np.ndarray:
+    cu = [0]
+    for (gt, gh, gw) in grids:
+        n = gt * gh * gw
+        cu.append(cu[-1] + (n + (1 if (use_cls and n) else 0)))
+    return np.asarray(cu, np.int64)
+
+
+def embed(patches_per_item: List[np.ndarray], grids, desc, weights, dtype=np.float64):
+    """Patch embedding + CLS + position term -> hidden rows [T, d]."""
+    wpe = weights["w_pe"].astype(dtype)
+    bpe = weights["b_pe"].astype(dtype)
+    segs = []
+    for p, (gt, gh, gw) in zip(patches_per_item, grids):
+        if gt * gh * gw == 0:
+            continue
+        x = p.astype(dtype) @ wpe.T + bpe
+        if desc.use_cls:
+            x = np.concatenate([weights["cls"].astype(dtype)[None, :], x], 0)
+        segs.append(x)
+    if not segs:
+        return np.zeros((0, desc.d), dtype)
+    x = np.concatenate(segs, 0)
+    return x + position_rows(desc, grids, weights, dtype)
+
+
+def encoder_block(x, cu, desc, weights, l, dtype=np.float64):
+    g = lambda n: weights[f"l{l}.{n}"].astype(dtype)
+    d = desc.d
+    h = layernorm(x, g("ln1_g"), g("ln1_b"), desc.ln_eps)
+    qkv = h @ g("w_qkv").T + g("b_qkv")
+    o = attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], cu, desc.heads)
+    x = x + (o @ g("w_o").T + g("b_o"))
+    h = layernorm(x, g("ln2_g"), g("ln2_b"), desc.ln_eps)
+    h = gelu(h @ g("w_1").T + g("b_1"))
+    x = x + (h @ g("w_2").T + g("b_2"))
+    return x
+
+
+def encode(patches_per_item, grids, desc, weights, dtype=np.float64, progress=None):
+    """Patches of every request -> encoder output [T, d] (segments concatenated
+    in request order; requests without frames contribute no rows)."""
+    cu = cu_seqlens_of(grids, desc.use_cls)
+    x = embed(patches_per_item, grids, desc, weights, dtype)
+    for l in range(desc.layers):
+        x = encoder_block(x, cu, desc, weights, l, dtype)
+        if progress:
+            progress(l)
+    if desc.final_ln:
+        x = layernorm(x, weights["lnf_g"].astype(dtype), weights["lnf_b"].astype(dtype), desc.ln_eps)
+    return x
+
+
+def merge_project(x, desc, weights, dtype=np.float64):
+    """Encoder output [T, d] -> [T/merge^2, out_dim]."""
+    g = lambda n: weights[n].astype(dtype)
+    m2 = desc.merge * desc.merge
+    y = layernorm(x.astype(dtype), g("lnm_g"), g("lnm_b"), desc.ln_eps)
+    y = y.reshape(x.shape[0] // m2, m2 * desc.d)
+    y = gelu(y @ g("w_m1").T + g("b_m1"))
+    return y @ g("w_m2").T + g("b_m2")
