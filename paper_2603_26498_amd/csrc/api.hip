@@ -1,0 +1,660 @@
+// Host side of the C ABI declared in include/tcmv.h: context, plan construction
+// (pure host logic), workspace carving and the sequence of kernel launches that
+// makes up each stage.  No arithmetic of the method happens here.
+#include "../../include/tcmv.h"
+#include "tcmv_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace tcmv;
+
+struct tcmv_ctx {
+  tcmv_model_desc desc;
+  int64_t k, k_pad;
+  bool has_weights = false;
+  tcmv_weights w;
+  std::vector<const void*> layer;   // layers*12 device pointers (copied)
+  std::string err;
+};
+
+struct tcmv_plan {
+  tcmv_ctx* ctx;
+  std::vector<ItemDev> items;
+  std::vector<int64_t> cu;            // n_items + 1
+  std::vector<int32_t> prow_item, prow_thw, prow_dst, prow_pos;
+  std::vector<int32_t> row_vcol;      // hidden row -> column in the transposed-V buffer
+  std::vector<int32_t> cls_rows;
+  std::vector<AttnWork> work;
+  std::vector<float> lut;             // [3][256]
+  int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
+  int n_segments = 0;
+  // device copy (allocated on first device use)
+  uint8_t* d_meta = nullptr;
+  size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
+         off_cls = 0, off_work = 0, off_lut = 0, meta_bytes = 0;
+};
+
+namespace {
+
+thread_local std::string g_create_err;   // reason of the last failed tcmv_create on this thread
+
+int fail(tcmv_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  return code;
+}
+int fail_hip(tcmv_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, TCMV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+float round_bf16_host(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+int validate_desc(const tcmv_model_desc* d, std::string& why) {
+  if (!d) { why = "null description"; return TCMV_E_INVALID_ARG; }
+  if (d->dtype != TCMV_F32 && d->dtype != TCMV_BF16) { why = "unknown dtype"; return TCMV_E_INVALID_ARG; }
+  if (d->layers < 0 || d->d <= 0 || d->heads <= 0 || d->mlp <= 0 || d->patch <= 0 || d->tpatch <= 0 ||
+      d->out_dim < 0 || d->max_pos < 0) { why = "non-positive size"; return TCMV_E_INVALID_ARG; }
+  if (d->merge != 1 && d->merge != 2) { why = "merge must be 1 or 2"; return TCMV_E_INVALID_ARG; }
+  if (d->pos < TCMV_POS_NONE || d->pos > TCMV_POS_SEPARABLE_2D) { why = "unknown position scheme"; return TCMV_E_INVALID_ARG; }
+  if (d->d % d->heads) { why = "d not divisible by heads"; return TCMV_E_INVALID_ARG; }
+  if (!(d->ln_eps >= 0.f)) { why = "negative ln_eps"; return TCMV_E_INVALID_ARG; }
+  for (int c = 0; c < 3; ++c)
+    if (!(d->std[c] > 0.f) || !std::isfinite(d->mean[c])) { why = "bad mean/std"; return TCMV_E_INVALID_ARG; }
+  if (d->pos != TCMV_POS_NONE && d->max_pos <= 0) { why = "position table without rows"; return TCMV_E_INVALID_ARG; }
+  if (d->pos == TCMV_POS_SEPARABLE_2D && d->use_cls) { why = "CLS with separable 2-D positions"; return TCMV_E_UNSUPPORTED; }
+  if (d->out_dim && d->use_cls) { why = "projector with CLS rows"; return TCMV_E_UNSUPPORTED; }
+  if (d->patch > 32) { why = "patch above 32"; return TCMV_E_UNSUPPORTED; }
+  if (d->d % 4 || d->d > 2048) { why = "d must be a multiple of 4, at most 2048"; return TCMV_E_UNSUPPORTED; }
+  const int dh = d->d / d->heads;
+  if (d->dtype == TCMV_BF16) {
+    if (dh != 32 && dh != 64 && dh != 80 && dh != 96) { why = "bf16 head size must be 32, 64, 80 or 96"; return TCMV_E_UNSUPPORTED; }
+    if (d->d % 64 || d->mlp % 64 || d->out_dim % 8) { why = "bf16 path needs d, mlp multiples of 64 and out_dim of 8"; return TCMV_E_UNSUPPORTED; }
+  } else {
+    if (dh % 16 || dh > 128) { why = "fp32 head size must be a multiple of 16, at most 128"; return TCMV_E_UNSUPPORTED; }
+  }
+  return TCMV_OK;
+}
+
+int64_t k_of(const tcmv_model_desc& d) { return 3LL * d.tpatch * d.patch * d.patch; }
+int64_t k_pad_of(const tcmv_model_desc& d) {
+  const int64_t k = k_of(d);
+  return d.dtype == TCMV_BF16 ? (k + 63) / 64 * 64 : (k + 1) / 2 * 2;
+}
+
+size_t elt(const tcmv_ctx* c) { return c->desc.dtype == TCMV_BF16 ? 2 : 4; }
+
+struct EncodeWs { size_t xn, qkv, vt, h, total; };
+EncodeWs encode_ws(const tcmv_plan* p) {
+  const tcmv_model_desc& d = p->ctx->desc;
+  const size_t e = elt(p->ctx);
+  const size_t T = (size_t)p->n_tokens;
+  EncodeWs w{};
+  size_t off = 0;
+  w.xn = off; off = align_up(off + T * d.d * e, 256);
+  if (d.dtype == TCMV_BF16) {
+    w.qkv = off; off = align_up(off + T * 2 * d.d * e, 256);
+    w.vt = off; off = align_up(off + (size_t)d.d * p->t_vpad * e, 256);
+  } else {
+    w.qkv = off; off = align_up(off + T * 3 * d.d * e, 256);
+    w.vt = off;
+  }
+  w.h = off; off = align_up(off + T * d.mlp * e, 256);
+  w.total = off;
+  return w;
+}
+struct MergeWs { size_t y, h, total; };
+MergeWs merge_ws(const tcmv_plan* p) {
+  const tcmv_model_desc& d = p->ctx->desc;
+  const size_t e = elt(p->ctx);
+  const size_t T = (size_t)p->n_tokens;
+  MergeWs w{};
+  size_t off = 0;
+  w.y = off; off = align_up(off + T * d.d * e, 256);
+  w.h = off; off = align_up(off + T * d.d * e, 256);   // [T/m2, m2*d]
+  w.total = off;
+  return w;
+}
+
+template <class T>
+size_t place(size_t& off, const std::vector<T>& v) {
+  const size_t at = off;
+  off = align_up(off + std::max<size_t>(v.size() * sizeof(T), 16), 256);
+  return at;
+}
+
+int ensure_uploaded(tcmv_ctx* ctx, tcmv_plan* p) {
+  if (p->d_meta || p->meta_bytes == 0) return TCMV_OK;
+  std::vector<uint8_t> blob(p->meta_bytes, 0);
+  auto put = [&](size_t off, const void* src, size_t n) { if (n) std::memcpy(blob.data() + off, src, n); };
+  put(p->off_items, p->items.data(), p->items.size() * sizeof(ItemDev));
+  put(p->off_prow_item, p->prow_item.data(), p->prow_item.size() * 4);
+  put(p->off_prow_thw, p->prow_thw.data(), p->prow_thw.size() * 4);
+  put(p->off_prow_dst, p->prow_dst.data(), p->prow_dst.size() * 4);
+  put(p->off_prow_pos, p->prow_pos.data(), p->prow_pos.size() * 4);
+  put(p->off_vcol, p->row_vcol.data(), p->row_vcol.size() * 4);
+  put(p->off_cls, p->cls_rows.data(), p->cls_rows.size() * 4);
+  put(p->off_work, p->work.data(), p->work.size() * sizeof(AttnWork));
+  put(p->off_lut, p->lut.data(), p->lut.size() * 4);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_meta), p->meta_bytes);
+  if (e != hipSuccess) { p->d_meta = nullptr; return fail_hip(ctx, e, "hipMalloc(plan metadata)"); }
+  e = hipMemcpy(p->d_meta, blob.data(), p->meta_bytes, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(p->d_meta);
+    p->d_meta = nullptr;
+    return fail_hip(ctx, e, "hipMemcpy(plan metadata)");
+  }
+  return TCMV_OK;
+}
+
+template <class T>
+const T* dev(const tcmv_plan* p, size_t off) { return reinterpret_cast<const T*>(p->d_meta + off); }
+
+void build_work(std::vector<AttnWork>& work, const std::vector<int64_t>& seg_start, const std::vector<int64_t>& seg_len,
+                const std::vector<int64_t>& seg_v0, int bq) {
+  work.clear();
+  for (size_t s = 0; s < seg_start.size(); ++s) {
+    for (int64_t q = 0; q < seg_len[s]; q += bq) {
+      AttnWork w{};
+      w.q0 = (int)(seg_start[s] + q);
+      w.nq = (int)std::min<int64_t>(bq, seg_len[s] - q);
+      w.seg_start = (int)seg_start[s];
+      w.seg_len = (int)seg_len[s];
+      w.v0 = (int)seg_v0[s];
+      work.push_back(w);
+    }
+  }
+  // longest segments first: the work per tile is proportional to the segment length
+  std::stable_sort(work.begin(), work.end(), [](const AttnWork& a, const AttnWork& b) { return a.seg_len > b.seg_len; });
+}
+
+hipError_t run_gemm(const tcmv_ctx* ctx, const GemmArgs& g, hipStream_t s) {
+  return ctx->desc.dtype == TCMV_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tcmv_version(void) { return 100; }
+
+const char* tcmv_error_name(int code) {
+  switch (code) {
+    case TCMV_OK: return "TCMV_OK";
+    case TCMV_E_INVALID_ARG: return "TCMV_E_INVALID_ARG";
+    case TCMV_E_BAD_SHAPE: return "TCMV_E_BAD_SHAPE";
+    case TCMV_E_WORKSPACE_TOO_SMALL: return "TCMV_E_WORKSPACE_TOO_SMALL";
+    case TCMV_E_NO_WEIGHTS: return "TCMV_E_NO_WEIGHTS";
+    case TCMV_E_HIP: return "TCMV_E_HIP";
+    case TCMV_E_UNSUPPORTED: return "TCMV_E_UNSUPPORTED";
+    default: return "TCMV_E_UNKNOWN";
+  }
+}
+
+int64_t tcmv_k_pad(const tcmv_model_desc* desc) {
+  std::string why;
+  const int rc = validate_desc(desc, why);
+  if (rc != TCMV_OK) return rc;
+  return k_pad_of(*desc);
+}
+
+int tcmv_create(const tcmv_model_desc* desc, tcmv_ctx** out) {
+  if (!out) return TCMV_E_INVALID_ARG;
+  *out = nullptr;
+  std::string why;
+  const int rc = validate_desc(desc, why);
+  if (rc != TCMV_OK) { g_create_err = why; return rc; }
+  tcmv_ctx* c = new (std::nothrow) tcmv_ctx();
+  if (!c) return TCMV_E_INVALID_ARG;
+  c->desc = *desc;
+  c->k = k_of(*desc);
+  c->k_pad = k_pad_of(*desc);
+  std::memset(&c->w, 0, sizeof(c->w));
+  *out = c;
+  return TCMV_OK;
+}
+
+void tcmv_destroy(tcmv_ctx* ctx) { delete ctx; }
+
+const char* tcmv_last_error(const tcmv_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+int tcmv_set_weights(tcmv_ctx* ctx, const tcmv_weights* w) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  if (!w) return fail(ctx, TCMV_E_INVALID_ARG, "null weights");
+  const tcmv_model_desc& d = ctx->desc;
+  if (!w->w_pe || !w->b_pe) return fail(ctx, TCMV_E_INVALID_ARG, "w_pe / b_pe missing");
+  if (d.use_cls && !w->cls) return fail(ctx, TCMV_E_INVALID_ARG, "cls missing");
+  if (d.pos != TCMV_POS_NONE && !w->pos0) return fail(ctx, TCMV_E_INVALID_ARG, "pos0 missing");
+  if (d.pos == TCMV_POS_SEPARABLE_2D && !w->pos1) return fail(ctx, TCMV_E_INVALID_ARG, "pos1 missing");
+  if (d.layers > 0 && !w->layer) return fail(ctx, TCMV_E_INVALID_ARG, "layer array missing");
+  for (int i = 0; i < d.layers * 12; ++i)
+    if (!w->layer[i]) return fail(ctx, TCMV_E_INVALID_ARG, "a layer parameter is missing");
+  if (d.final_ln && (!w->lnf_g || !w->lnf_b)) return fail(ctx, TCMV_E_INVALID_ARG, "final LayerNorm missing");
+  if (d.out_dim && (!w->lnm_g || !w->lnm_b || !w->w_m1 || !w->b_m1 || !w->w_m2 || !w->b_m2))
+    return fail(ctx, TCMV_E_INVALID_ARG, "projector parameters missing");
+  ctx->w = *w;
+  ctx->layer.assign(w->layer, w->layer + (size_t)d.layers * 12);
+  ctx->w.layer = ctx->layer.data();
+  ctx->has_weights = true;
+  return TCMV_OK;
+}
+
+int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_plan** out) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  if (!out || n_items < 0 || (n_items > 0 && !items)) return fail(ctx, TCMV_E_INVALID_ARG, "bad plan arguments");
+  *out = nullptr;
+  const tcmv_model_desc& d = ctx->desc;
+  const int pm = d.patch * d.merge;
+  tcmv_plan* p = new (std::nothrow) tcmv_plan();
+  if (!p) return fail(ctx, TCMV_E_INVALID_ARG, "out of host memory");
+  p->ctx = ctx;
+  p->cu.assign(1, 0);
+  std::vector<int64_t> seg_start, seg_len, seg_v0;
+  auto bad = [&](const std::string& m) { delete p; return fail(ctx, TCMV_E_BAD_SHAPE, m); };
+  for (int i = 0; i < n_items; ++i) {
+    const tcmv_item& it = items[i];
+    ItemDev di{};
+    di.frames = it.d_frames;
+    if (it.n_frames < 0) { delete p; return fail(ctx, TCMV_E_INVALID_ARG, "negative frame count"); }
+    if (it.modality < TCMV_TEXT || it.modality > TCMV_VIDEO) { delete p; return fail(ctx, TCMV_E_INVALID_ARG, "unknown modality"); }
+    if (it.n_frames == 0) {          // text: no tokens
+      p->items.push_back(di);
+      p->cu.push_back(p->cu.back());
+      continue;
+    }
+    if (it.dst_h <= 0 || it.dst_w <= 0 || it.dst_h % pm || it.dst_w % pm)
+      return bad("target size must be a positive multiple of patch*merge (item " + std::to_string(i) + ")");
+    if (it.src_h < 1 || it.src_w < 1) return bad("source size below 1");
+    if (it.n_frames > 1 && it.n_frames % d.tpatch) return bad("video length not a multiple of the temporal patch");
+    di.n_frames = it.n_frames; di.src_h = it.src_h; di.src_w = it.src_w; di.dst_h = it.dst_h; di.dst_w = it.dst_w;
+    di.gt = it.n_frames == 1 ? 1 : it.n_frames / d.tpatch;
+    di.gh = it.dst_h / d.patch; di.gw = it.dst_w / d.patch;
+    di.resized = (it.src_h != it.dst_h) || (it.src_w != it.dst_w);
+    if (di.gh > 255 || di.gw > 255 || di.gt > 32767) return bad("grid too large (side above 255 or more than 32767 frame groups)");
+    if ((int64_t)it.src_h * it.src_w > (1LL << 28) || (int64_t)it.src_h * it.dst_h > (1LL << 28) ||
+        (int64_t)it.src_w * it.dst_w > (1LL << 28)) return bad("frame too large");
+    const int64_t n = (int64_t)di.gt * di.gh * di.gw;
+    const int64_t rows = n + (d.use_cls ? 1 : 0);
+    if (d.pos == TCMV_POS_LEARNED_1D && rows > d.max_pos) return bad("segment longer than the position table");
+    if (d.pos == TCMV_POS_SEPARABLE_2D && (di.gh > d.max_pos || di.gw > d.max_pos)) return bad("grid side above the position table");
+    if (p->cu.back() + rows > (1LL << 30)) return bad("too many tokens");
+    const int64_t row0 = p->cu.back();
+    const int item_idx = (int)p->items.size();
+    if (d.use_cls) p->cls_rows.push_back((int32_t)row0);
+    int64_t local = d.use_cls ? 1 : 0;
+    auto emit = [&](int t, int h, int w) {
+      p->prow_item.push_back(item_idx);
+      p->prow_thw.push_back((t << 16) | (h << 8) | w);
+      p->prow_dst.push_back((int32_t)(row0 + local));
+      int32_t pos = 0;
+      if (d.pos == TCMV_POS_LEARNED_1D) pos = (int32_t)local;
+      else if (d.pos == TCMV_POS_SEPARABLE_2D) pos = h | (w << 16);
+      p->prow_pos.push_back(pos);
+      ++local;
+    };
+    for (int t = 0; t < di.gt; ++t) {
+      if (d.merge == 1) {
+        for (int h = 0; h < di.gh; ++h)
+          for (int w = 0; w < di.gw; ++w) emit(t, h, w);
+      } else {
+        for (int hb = 0; hb < di.gh / 2; ++hb)
+          for (int wb = 0; wb < di.gw / 2; ++wb)
+            for (int hi = 0; hi < 2; ++hi)
+              for (int wi = 0; wi < 2; ++wi) emit(t, 2 * hb + hi, 2 * wb + wi);
+      }
+    }
+    seg_start.push_back(row0);
+    seg_len.push_back(rows);
+    seg_v0.push_back(p->t_vpad);
+    for (int64_t r = 0; r < rows; ++r) p->row_vcol.push_back((int32_t)(p->t_vpad + r));
+    p->t_vpad += (rows + kVtAlign - 1) / kVtAlign * kVtAlign;
+    p->items.push_back(di);
+    p->cu.push_back(row0 + rows);
+  }
+  p->n_patch_rows = (int64_t)p->prow_item.size();
+  p->n_tokens = p->cu.back();
+  p->n_segments = (int)seg_start.size();
+  build_work(p->work, seg_start, seg_len, seg_v0, d.dtype == TCMV_BF16 ? kAttnBQ_bf16 : kAttnBQ_f32);
+  // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
+  p->lut.resize(3 * 256);
+  for (int c = 0; c < 3; ++c)
+    for (int v = 0; v < 256; ++v) {
+      float x = (float)(((double)v / 255.0 - (double)d.mean[c]) / (double)d.std[c]);
+      if (d.dtype == TCMV_BF16) x = round_bf16_host(x);
+      p->lut[c * 256 + v] = x;
+    }
+  size_t off = 0;
+  p->off_items = place(off, p->items);
+  p->off_prow_item = place(off, p->prow_item);
+  p->off_prow_thw = place(off, p->prow_thw);
+  p->off_prow_dst = place(off, p->prow_dst);
+  p->off_prow_pos = place(off, p->prow_pos);
+  p->off_vcol = place(off, p->row_vcol);
+  p->off_cls = place(off, p->cls_rows);
+  p->off_work = place(off, p->work);
+  p->off_lut = place(off, p->lut);
+  p->meta_bytes = off;
+  *out = p;
+  return TCMV_OK;
+}
+
+void tcmv_plan_destroy(tcmv_plan* plan) {
+  if (!plan) return;
+  if (plan->d_meta) (void)hipFree(plan->d_meta);
+  delete plan;
+}
+
+int tcmv_plan_query(const tcmv_plan* p, tcmv_plan_info* info) {
+  if (!p || !info) return TCMV_E_INVALID_ARG;
+  const tcmv_model_desc& d = p->ctx->desc;
+  std::memset(info, 0, sizeof(*info));
+  info->n_patch_rows = p->n_patch_rows;
+  info->n_tokens = p->n_tokens;
+  const int m2 = d.merge * d.merge;
+  info->n_out_tokens = d.out_dim ? p->n_tokens / m2 : 0;
+  info->k = p->ctx->k;
+  info->k_pad = p->ctx->k_pad;
+  info->patches_bytes = (size_t)p->n_patch_rows * p->ctx->k_pad * elt(p->ctx);
+  info->hidden_bytes = (size_t)p->n_tokens * d.d * 4;
+  info->out_bytes = (size_t)info->n_out_tokens * d.out_dim * elt(p->ctx);
+  info->encode_workspace_bytes = encode_ws(p).total;
+  info->merge_workspace_bytes = d.out_dim ? merge_ws(p).total : 0;
+  info->n_items = (int)p->items.size();
+  info->n_segments = p->n_segments;
+  return TCMV_OK;
+}
+
+const int64_t* tcmv_plan_cu_seqlens(const tcmv_plan* p) { return p ? p->cu.data() : nullptr; }
+
+int64_t tcmv_plan_row_map(const tcmv_plan* p, int which, const int32_t** out) {
+  if (!p || !out) return TCMV_E_INVALID_ARG;
+  const std::vector<int32_t>* v = nullptr;
+  switch (which) {
+    case 0: v = &p->prow_thw; break;
+    case 1: v = &p->prow_dst; break;
+    case 2: v = &p->prow_pos; break;
+    default: return TCMV_E_INVALID_ARG;
+  }
+  *out = v->data();
+  return (int64_t)v->size();
+}
+
+int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
+  if (p->n_patch_rows == 0) return TCMV_OK;
+  if (!d_patches) return fail(ctx, TCMV_E_INVALID_ARG, "null patch buffer");
+  for (const ItemDev& it : p->items)
+    if (it.n_frames > 0 && !it.frames) return fail(ctx, TCMV_E_INVALID_ARG, "an item with frames has a null frame pointer");
+  int rc = ensure_uploaded(ctx, p);
+  if (rc != TCMV_OK) return rc;
+  PreprocArgs a{};
+  a.items = dev<ItemDev>(p, p->off_items);
+  a.prow_item = dev<int32_t>(p, p->off_prow_item);
+  a.prow_thw = dev<int32_t>(p, p->off_prow_thw);
+  a.lut = dev<float>(p, p->off_lut);
+  a.patches = d_patches;
+  a.rows = p->n_patch_rows;
+  a.patch = ctx->desc.patch; a.tpatch = ctx->desc.tpatch;
+  a.k = (int)ctx->k; a.k_pad = (int)ctx->k_pad;
+  a.out_bf16 = ctx->desc.dtype == TCMV_BF16;
+  hipError_t e = launch_preprocess(a, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "preprocess launch");
+  return TCMV_OK;
+}
+
+int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidden, void* d_workspace,
+                size_t workspace_bytes, void* stream) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
+  if (!ctx->has_weights) return fail(ctx, TCMV_E_NO_WEIGHTS, "tcmv_set_weights has not been called");
+  if (p->n_tokens == 0) return TCMV_OK;
+  if (!d_patches || !d_hidden || !d_workspace) return fail(ctx, TCMV_E_INVALID_ARG, "null buffer");
+  if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return fail(ctx, TCMV_E_INVALID_ARG, "workspace not 256-byte aligned");
+  const EncodeWs ws = encode_ws(p);
+  if (workspace_bytes < ws.total) return fail(ctx, TCMV_E_WORKSPACE_TOO_SMALL, "encode workspace too small");
+  int rc = ensure_uploaded(ctx, p);
+  if (rc != TCMV_OK) return rc;
+
+  const tcmv_model_desc& d = ctx->desc;
+  const bool bf = d.dtype == TCMV_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* wsb = reinterpret_cast<uint8_t*>(d_workspace);
+  void* xn = wsb + ws.xn;
+  void* qkv = wsb + ws.qkv;
+  void* vt = wsb + ws.vt;
+  void* hbuf = wsb + ws.h;
+  float* x = reinterpret_cast<float*>(d_hidden);
+  const int64_t T = p->n_tokens;
+  const int dh = d.d / d.heads;
+  hipError_t e;
+#define TCMV_CHECK(call, what) do { e = (call); if (e != hipSuccess) return fail_hip(ctx, e, what); } while (0)
+
+  // patch embedding (+ position), CLS rows
+  {
+    GemmArgs g{};
+    g.a = d_patches; g.lda = ctx->k_pad; g.w = ctx->w.w_pe; g.bias = reinterpret_cast<const float*>(ctx->w.b_pe);
+    g.c = x; g.ldc = d.d; g.m = p->n_patch_rows; g.n = d.d; g.k = (int)ctx->k_pad; g.epi = EPI_EMBED;
+    g.dst_row = dev<int32_t>(p, p->off_prow_dst); g.pos_idx = dev<int32_t>(p, p->off_prow_pos);
+    g.pos0 = reinterpret_cast<const float*>(ctx->w.pos0); g.pos1 = reinterpret_cast<const float*>(ctx->w.pos1);
+    g.pos_kind = d.pos;
+    TCMV_CHECK(run_gemm(ctx, g, s), "patch-embed GEMM");
+    if (d.use_cls)
+      TCMV_CHECK(launch_cls_rows(x, dev<int32_t>(p, p->off_cls), (int)p->cls_rows.size(),
+                                 reinterpret_cast<const float*>(ctx->w.cls),
+                                 d.pos == TCMV_POS_LEARNED_1D ? reinterpret_cast<const float*>(ctx->w.pos0) : nullptr,
+                                 d.d, s), "CLS rows");
+  }
+  for (int l = 0; l < d.layers; ++l) {
+    const void* const* L = ctx->layer.data() + (size_t)l * 12;
+    auto f = [&](int j) { return reinterpret_cast<const float*>(L[j]); };
+    TCMV_CHECK(launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s), "LN1");
+    {
+      GemmArgs g{};
+      g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * d.d; g.k = d.d;
+      g.c = qkv; g.epi = EPI_QKV;
+      if (bf) { g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->t_vpad; g.vcol = dev<int32_t>(p, p->off_vcol); }
+      else { g.ldc = 3 * d.d; }
+      TCMV_CHECK(run_gemm(ctx, g, s), "QKV GEMM");
+    }
+    {
+      AttnArgs a{};
+      a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size();
+      a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = d.d;
+      if (bf) {
+        const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
+        a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->t_vpad;
+        a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
+        TCMV_CHECK(launch_attn_bf16(a, s), "attention");
+      } else {
+        const float* q3 = reinterpret_cast<const float*>(qkv);
+        a.q = q3; a.k = q3 + d.d; a.ldqk = 3 * d.d; a.v = q3 + 2 * d.d; a.ldv = 3 * d.d;
+        a.scale = (float)(1.0 / std::sqrt((double)dh));
+        TCMV_CHECK(launch_attn_f32(a, s), "attention");
+      }
+    }
+    {
+      GemmArgs g{};
+      g.a = xn; g.lda = d.d; g.w = L[4]; g.bias = f(5); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.d;
+      g.epi = EPI_RESID;
+      TCMV_CHECK(run_gemm(ctx, g, s), "out-proj GEMM");
+    }
+    TCMV_CHECK(launch_layernorm(x, f(6), f(7), xn, T, d.d, d.ln_eps, bf, s), "LN2");
+    {
+      GemmArgs g{};
+      g.a = xn; g.lda = d.d; g.w = L[8]; g.bias = f(9); g.c = hbuf; g.ldc = d.mlp; g.m = T; g.n = d.mlp; g.k = d.d;
+      g.epi = EPI_GELU;
+      TCMV_CHECK(run_gemm(ctx, g, s), "fc1 GEMM");
+    }
+    {
+      GemmArgs g{};
+      g.a = hbuf; g.lda = d.mlp; g.w = L[10]; g.bias = f(11); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.mlp;
+      g.epi = EPI_RESID;
+      TCMV_CHECK(run_gemm(ctx, g, s), "fc2 GEMM");
+    }
+  }
+  if (d.final_ln)
+    TCMV_CHECK(launch_layernorm(x, reinterpret_cast<const float*>(ctx->w.lnf_g), reinterpret_cast<const float*>(ctx->w.lnf_b),
+                                x, T, d.d, d.ln_eps, 0, s), "final LN");
+  return TCMV_OK;
+}
+
+int tcmv_merge_project(tcmv_ctx* ctx, tcmv_plan* p, const void* d_hidden, void* d_out, void* d_workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
+  const tcmv_model_desc& d = ctx->desc;
+  if (!d.out_dim) return fail(ctx, TCMV_E_UNSUPPORTED, "model has no projector");
+  if (!ctx->has_weights) return fail(ctx, TCMV_E_NO_WEIGHTS, "tcmv_set_weights has not been called");
+  if (p->n_tokens == 0) return TCMV_OK;
+  if (!d_hidden || !d_out || !d_workspace) return fail(ctx, TCMV_E_INVALID_ARG, "null buffer");
+  if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return fail(ctx, TCMV_E_INVALID_ARG, "workspace not 256-byte aligned");
+  const MergeWs ws = merge_ws(p);
+  if (workspace_bytes < ws.total) return fail(ctx, TCMV_E_WORKSPACE_TOO_SMALL, "merge workspace too small");
+  const bool bf = d.dtype == TCMV_BF16;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* wsb = reinterpret_cast<uint8_t*>(d_workspace);
+  void* y = wsb + ws.y;
+  void* h = wsb + ws.h;
+  const int m2 = d.merge * d.merge;
+  const int64_t T = p->n_tokens, Tm = T / m2;
+  const int dm = d.d * m2;
+  hipError_t e;
+  TCMV_CHECK(launch_layernorm(reinterpret_cast<const float*>(d_hidden), reinterpret_cast<const float*>(ctx->w.lnm_g),
+                              reinterpret_cast<const float*>(ctx->w.lnm_b), y, T, d.d, d.ln_eps, bf, s), "merger LN");
+  {
+    GemmArgs g{};
+    g.a = y; g.lda = dm; g.w = ctx->w.w_m1; g.bias = reinterpret_cast<const float*>(ctx->w.b_m1);
+    g.c = h; g.ldc = dm; g.m = Tm; g.n = dm; g.k = dm; g.epi = EPI_GELU;
+    TCMV_CHECK(run_gemm(ctx, g, s), "merger fc1 GEMM");
+  }
+  {
+    GemmArgs g{};
+    g.a = h; g.lda = dm; g.w = ctx->w.w_m2; g.bias = reinterpret_cast<const float*>(ctx->w.b_m2);
+    g.c = d_out; g.ldc = d.out_dim; g.m = Tm; g.n = d.out_dim; g.k = dm; g.epi = EPI_STORE;
+    TCMV_CHECK(run_gemm(ctx, g, s), "merger fc2 GEMM");
+  }
+  return TCMV_OK;
+}
+
+// ---- single operators ------------------------------------------------------
+
+int tcmv_op_layernorm(int dtype, const float* d_x, const float* d_gamma, const float* d_beta, void* d_y,
+                      int64_t rows, int d, float eps, void* stream) {
+  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || rows < 0 || d <= 0) return TCMV_E_INVALID_ARG;
+  if (rows == 0) return TCMV_OK;
+  if (!d_x || !d_gamma || !d_beta || !d_y) return TCMV_E_INVALID_ARG;
+  if (d % 4 || d > 2048) return TCMV_E_UNSUPPORTED;
+  return launch_layernorm(d_x, d_gamma, d_beta, d_y, rows, d, eps, dtype == TCMV_BF16, (hipStream_t)stream) == hipSuccess
+             ? TCMV_OK : TCMV_E_HIP;
+}
+
+int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, const float* d_bias, void* d_c,
+                 int64_t m, int n, int k, void* stream) {
+  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || epilogue < 0 || epilogue > 2 || m < 0 || n <= 0 || k <= 0)
+    return TCMV_E_INVALID_ARG;
+  if (m == 0) return TCMV_OK;
+  if (!d_a || !d_w || !d_c) return TCMV_E_INVALID_ARG;
+  if (dtype == TCMV_BF16 && (k % 64 || n % 8)) return TCMV_E_UNSUPPORTED;
+  GemmArgs g{};
+  g.a = d_a; g.lda = k; g.w = d_w; g.bias = d_bias; g.c = d_c; g.ldc = n; g.m = m; g.n = n; g.k = k; g.epi = epilogue;
+  const hipError_t e = dtype == TCMV_BF16 ? launch_gemm_bf16(g, (hipStream_t)stream) : launch_gemm_f32(g, (hipStream_t)stream);
+  return e == hipSuccess ? TCMV_OK : TCMV_E_HIP;
+}
+
+namespace {
+struct OpAttnLayout { size_t vcol, work, vt, total; int64_t t_vpad; int64_t T; };
+OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int heads, std::vector<int32_t>* vcol,
+                            std::vector<AttnWork>* work) {
+  OpAttnLayout L{};
+  std::vector<int64_t> ss, sl, sv;
+  int64_t vp = 0;
+  for (int s = 0; s < n_seg; ++s) {
+    const int64_t len = cu[s + 1] - cu[s];
+    if (len <= 0) continue;
+    ss.push_back(cu[s]); sl.push_back(len); sv.push_back(vp);
+    vp += (len + kVtAlign - 1) / kVtAlign * kVtAlign;
+  }
+  L.T = n_seg > 0 ? cu[n_seg] : 0;
+  L.t_vpad = vp;
+  std::vector<AttnWork> wtmp;
+  build_work(wtmp, ss, sl, sv, dtype == TCMV_BF16 ? kAttnBQ_bf16 : kAttnBQ_f32);
+  if (vcol) {
+    vcol->assign((size_t)L.T, 0);
+    for (size_t s = 0; s < ss.size(); ++s)
+      for (int64_t r = 0; r < sl[s]; ++r) (*vcol)[(size_t)(ss[s] + r)] = (int32_t)(sv[s] + r);
+  }
+  size_t off = 0;
+  L.vcol = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
+  L.work = off; off = align_up(off + std::max<size_t>(wtmp.size() * sizeof(AttnWork), 16), 256);
+  L.vt = off;
+  if (dtype == TCMV_BF16) off = align_up(off + (size_t)d * vp * 2, 256);
+  L.total = off;
+  if (work) work->swap(wtmp);
+  return L;
+}
+bool cu_ok(const int64_t* cu, int n_seg) {
+  if (!cu || n_seg < 0) return false;
+  if (cu[0] != 0) return false;
+  for (int s = 0; s < n_seg; ++s)
+    if (cu[s + 1] < cu[s]) return false;
+  return cu[n_seg] < (1LL << 30);
+}
+}  // namespace
+
+size_t tcmv_op_attention_workspace(int dtype, const int64_t* cu_seqlens, int n_seg, int d, int heads) {
+  if (!cu_ok(cu_seqlens, n_seg) || d <= 0 || heads <= 0) return 0;
+  return op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr).total;
+}
+
+int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads,
+                      void* d_out, void* d_workspace, size_t workspace_bytes, void* stream) {
+  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || !cu_ok(cu_seqlens, n_seg) || d <= 0 || heads <= 0 || d % heads)
+    return TCMV_E_INVALID_ARG;
+  const int dh = d / heads;
+  if (dtype == TCMV_BF16 ? !(dh == 32 || dh == 64 || dh == 80 || dh == 96) : (dh % 16 || dh > 128)) return TCMV_E_UNSUPPORTED;
+  std::vector<int32_t> vcol;
+  std::vector<AttnWork> work;
+  const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work);
+  if (L.T == 0) return TCMV_OK;
+  if (!d_qkv || !d_out || !d_workspace) return TCMV_E_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return TCMV_E_INVALID_ARG;
+  if (workspace_bytes < L.total) return TCMV_E_WORKSPACE_TOO_SMALL;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* wsb = reinterpret_cast<uint8_t*>(d_workspace);
+  // index data: blocking copies (this entry point is for checking and timing one kernel)
+  if (hipMemcpy(wsb + L.vcol, vcol.data(), vcol.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
+  if (hipMemcpy(wsb + L.work, work.data(), work.size() * sizeof(AttnWork), hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
+  AttnArgs a{};
+  a.work = reinterpret_cast<const AttnWork*>(wsb + L.work); a.n_work = (int)work.size();
+  a.heads = heads; a.dh = dh; a.t_total = L.T; a.out = d_out; a.ldo = d;
+  hipError_t e;
+  if (dtype == TCMV_BF16) {
+    const uint16_t* q = reinterpret_cast<const uint16_t*>(d_qkv);
+    e = launch_transpose_v(q + 2 * d, 3 * d, reinterpret_cast<const int32_t*>(wsb + L.vcol), wsb + L.vt, L.t_vpad, L.T, d, s);
+    if (e != hipSuccess) return TCMV_E_HIP;
+    a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = wsb + L.vt; a.ldv = L.t_vpad;
+    a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
+    e = launch_attn_bf16(a, s);
+  } else {
+    const float* q = reinterpret_cast<const float*>(d_qkv);
+    a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = q + 2 * d; a.ldv = 3 * d;
+    a.scale = (float)(1.0 / std::sqrt((double)dh));
+    e = launch_attn_f32(a, s);
+  }
+  return e == hipSuccess ? TCMV_OK : TCMV_E_HIP;
+}
+
+}  // extern "C"

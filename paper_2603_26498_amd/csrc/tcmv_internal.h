@@ -1,0 +1,90 @@
+// Internal declarations shared by the host API and the kernel launchers.
+// Everything here is private to the library; the public surface is include/tcmv.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace tcmv {
+
+// ---- device-visible descriptors (plain data, uploaded with a plan) ----------
+struct ItemDev {
+  const uint8_t* frames;   // [n_frames, src_h, src_w, 3]
+  int n_frames, src_h, src_w, dst_h, dst_w;
+  int gt, gh, gw;          // token grid
+  int resized;             // src size differs from dst size
+  int pad_;
+};
+
+// One unit of attention work: a tile of query rows of one segment.
+struct AttnWork {
+  int q0;        // first query row (global row index)
+  int nq;        // valid query rows in this tile
+  int seg_start; // first row of the segment
+  int seg_len;   // rows of the segment
+  int v0;        // first column of the segment in the transposed-V buffer
+  int pad_[3];
+};
+
+enum Epilogue {
+  EPI_STORE = 0,   // C = acc + bias                      (bf16 or fp32 by path)
+  EPI_GELU = 1,    // C = gelu(acc + bias)
+  EPI_RESID = 2,   // C(fp32) += acc + bias
+  EPI_EMBED = 3,   // C(fp32)[dst_row[r]] = acc + bias + position term
+  EPI_QKV = 4      // columns < split: C ; columns >= split: transposed-V buffer
+};
+
+struct GemmArgs {
+  const void* a; int64_t lda;      // [m, k]
+  const void* w;                   // [n, k], ld = k
+  const float* bias;               // [n] or null
+  void* c; int64_t ldc;
+  int64_t m; int n; int k;
+  int epi;
+  // EPI_EMBED
+  const int32_t* dst_row; const int32_t* pos_idx; const float* pos0; const float* pos1; int pos_kind;
+  // EPI_QKV (bf16 path): q|k columns go to c (ldc), v columns to vt[col - split][vcol[row]]
+  int split; void* vt; int64_t ldvt; const int32_t* vcol;
+};
+
+struct AttnArgs {
+  const void* q; const void* k; int64_t ldqk;   // row stride (elements) of q and k
+  const void* v; int64_t ldv;                    // bf16 path: transposed V [d, ldv]; fp32 path: V rows [T, ldv]
+  void* out; int64_t ldo;
+  const AttnWork* work; int n_work;
+  int heads, dh;
+  int64_t t_total;                               // rows of q/k (for clamping)
+  float scale;
+};
+
+struct PreprocArgs {
+  const ItemDev* items;
+  const int32_t* prow_item;   // [rows]
+  const int32_t* prow_thw;    // [rows] t<<16 | h<<8 | w
+  const float* lut;           // [3][256] normalised values (already rounded to the storage type)
+  void* patches;              // [rows, k_pad]
+  int64_t rows;
+  int patch, tpatch, k, k_pad;
+  int out_bf16;
+};
+
+hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s);
+hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d,
+                            float eps, int out_bf16, hipStream_t s);
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
+// vt[c][vcol[r]] = v[r][c] for r < rows, c < d  (bf16)
+hipError_t launch_transpose_v(const void* v, int64_t ldv, const int32_t* vcol, void* vt, int64_t ldvt,
+                              int64_t rows, int d, hipStream_t s);
+// hidden[cls_rows[i]] = cls + pos0[0] (if pos0)
+hipError_t launch_cls_rows(float* hidden, const int32_t* cls_rows, int n, const float* cls,
+                           const float* pos0, int d, hipStream_t s);
+
+// Tile sizes the host must know about.
+constexpr int kAttnBQ_bf16 = 128;   // query rows per attention workgroup, bf16 path
+constexpr int kAttnBQ_f32 = 64;     // query rows per attention workgroup, fp32 path
+constexpr int kVtAlign = 64;        // segment starts in the transposed-V buffer are multiples of this
+
+}  // namespace tcmv

@@ -1,0 +1,164 @@
+"""Convenience layer over the C ABI: owns device memory through PyTorch (device
+memory and streams only) and marshals arguments.  No arithmetic of the method
+is done here; all of it runs in libtcmv.so."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: the vision path has no CPU fallback")
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream] = None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+class Plan:
+    def __init__(self, enc: "VisionEncoder", items, frame_tensors):
+        self.enc = enc
+        self.n_items = len(items)
+        self._frames = frame_tensors          # keep device frames alive
+        self.handle = B.tcmv_plan_create(enc.ctx, items)
+        self.info = B.tcmv_plan_query(self.handle)
+        self.cu_seqlens = B.tcmv_plan_cu_seqlens(self.handle, self.n_items)
+
+    def row_map(self, which):
+        return B.tcmv_plan_row_map(self.handle, which)
+
+    def close(self):
+        if self.handle is not None:
+            B.tcmv_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class VisionEncoder:
+    """desc: an object with the fields of tcmv_model_desc (e.g. workloads.ModelDesc).
+    weights: dict name -> numpy fp32 array, linear weights [out, in]; may be None
+    for plan-only (host) use."""
+
+    def __init__(self, desc, weights: Optional[Dict[str, np.ndarray]] = None, device="cuda:0"):
+        self.desc = desc
+        self.cdesc = B.make_desc(dtype=desc.dtype, layers=desc.layers, d=desc.d, heads=desc.heads, mlp=desc.mlp,
+                                 patch=desc.patch, tpatch=desc.tpatch, merge=desc.merge, out_dim=desc.out_dim,
+                                 use_cls=desc.use_cls, pos=desc.pos, max_pos=desc.max_pos, final_ln=desc.final_ln,
+                                 ln_eps=desc.ln_eps, mean=desc.mean, std=desc.std)
+        self.ctx = B.tcmv_create(self.cdesc)
+        self.k_pad = B.tcmv_k_pad(self.cdesc)
+        self.device = device
+        self.bf16 = desc.dtype == "bf16"
+        self._w = {}
+        self._layer_arr = None
+        if weights is not None:
+            self.set_weights(weights)
+
+    # -- parameters ---------------------------------------------------------------------------
+    def _mat(self, a: np.ndarray, pad_to: int = 0) -> torch.Tensor:
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+        if pad_to and t.shape[1] < pad_to:
+            t = torch.nn.functional.pad(t, (0, pad_to - t.shape[1]))
+        t = t.to(self.device)
+        return (t.to(torch.bfloat16) if self.bf16 else t).contiguous()
+
+    def _vec(self, a: np.ndarray) -> torch.Tensor:
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).contiguous()
+
+    def set_weights(self, w: Dict[str, np.ndarray]):
+        _require_gpu()
+        d = self.desc
+        T = self._w
+        T["w_pe"] = self._mat(w["w_pe"], self.k_pad)
+        T["b_pe"] = self._vec(w["b_pe"])
+        for n in ("cls", "pos0", "pos1", "lnf_g", "lnf_b", "lnm_g", "lnm_b", "b_m1", "b_m2"):
+            if n in w:
+                T[n] = self._vec(w[n])
+        for n in ("w_m1", "w_m2"):
+            if n in w:
+                T[n] = self._mat(w[n])
+        arr = (C.c_void_p * max(1, d.layers * 12))()
+        for l in range(d.layers):
+            for j, name in enumerate(B.LAYER_FIELDS):
+                key = f"l{l}.{name}"
+                T[key] = self._mat(w[key]) if name.startswith("w_") else self._vec(w[key])
+                arr[l * 12 + j] = T[key].data_ptr()
+        self._layer_arr = arr
+        cw = B.tcmv_weights()
+        for n in ("w_pe", "b_pe", "cls", "pos0", "pos1", "lnf_g", "lnf_b", "lnm_g", "lnm_b", "w_m1", "b_m1", "w_m2",
+                  "b_m2"):
+            setattr(cw, n, T[n].data_ptr() if n in T else None)
+        cw.layer = C.cast(arr, C.POINTER(C.c_void_p))
+        B.tcmv_set_weights(self.ctx, cw)
+
+    # -- requests -----------------------------------------------------------------------------
+    def plan(self, items: Sequence, upload: bool = True) -> Plan:
+        """items: objects with modality, n_frames, src_h, src_w, dst_h, dst_w, frames (numpy uint8 or None)."""
+        rows, keep = [], []
+        for it in items:
+            ptr = None
+            if it.n_frames > 0 and upload:
+                _require_gpu()
+                t = torch.from_numpy(np.ascontiguousarray(it.frames)).to(self.device)
+                keep.append(t)
+                ptr = t.data_ptr()
+            rows.append((it.modality, it.n_frames, it.src_h, it.src_w, it.dst_h, it.dst_w, ptr))
+        return Plan(self, rows, keep)
+
+    def preprocess(self, plan: Plan, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _require_gpu()
+        i = plan.info
+        if out is None:
+            out = torch.empty((i.n_patch_rows, i.k_pad), dtype=torch.bfloat16 if self.bf16 else torch.float32,
+                              device=self.device)
+        B.tcmv_preprocess(self.ctx, plan.handle, out, _stream_ptr())
+        return out
+
+    def workspace(self, nbytes: int) -> torch.Tensor:
+        return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+
+    def encode(self, plan: Plan, patches: torch.Tensor, hidden: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _require_gpu()
+        i = plan.info
+        if hidden is None:
+            hidden = torch.empty((i.n_tokens, self.desc.d), dtype=torch.float32, device=self.device)
+        if workspace is None:
+            workspace = self.workspace(i.encode_workspace_bytes)
+        B.tcmv_encode(self.ctx, plan.handle, patches, hidden, workspace, workspace.numel(), _stream_ptr())
+        return hidden
+
+    def merge_project(self, plan: Plan, hidden: torch.Tensor, out: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+        _require_gpu()
+        i = plan.info
+        if out is None:
+            out = torch.empty((i.n_out_tokens, self.desc.out_dim),
+                              dtype=torch.bfloat16 if self.bf16 else torch.float32, device=self.device)
+        if workspace is None:
+            workspace = self.workspace(i.merge_workspace_bytes)
+        B.tcmv_merge_project(self.ctx, plan.handle, hidden, out, workspace, workspace.numel(), _stream_ptr())
+        return out
+
+    def close(self):
+        if self.ctx is not None:
+            B.tcmv_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,145 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, validates descriptions and shapes, and its host-side plan
+(token order, cumulative lengths, index maps) agrees with the CPU reference."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import encoder as oe
+from oracle import preprocess as op
+from paper_2603_26498_amd import binding as B
+from paper_2603_26498_amd.runtime import VisionEncoder
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tcmv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(tcmv_[a-z0-9_]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.tcmv_version() >= 100
+    assert B.error_name(-2) == "TCMV_E_BAD_SHAPE"
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24
+    assert C.sizeof(B.tcmv_item) == 6 * 4 + 8
+    assert C.sizeof(B.tcmv_weights) == 14 * 8
+
+
+def test_description_validation():
+    with pytest.raises(B.TcmvError) as e:
+        B.tcmv_create(B.make_desc(dtype="bf16", layers=1, d=100, heads=3, mlp=64))
+    assert e.value.code == B.TCMV_E_INVALID_ARG
+    with pytest.raises(B.TcmvError) as e:
+        B.tcmv_create(B.make_desc(dtype="bf16", layers=1, d=192, heads=4, mlp=256))      # head size 48
+    assert e.value.code == B.TCMV_E_UNSUPPORTED and "head size" in str(e.value)
+    with pytest.raises(B.TcmvError):
+        B.tcmv_create(B.make_desc(dtype="f32", layers=1, d=64, heads=1, mlp=64, merge=3))
+    ctx = B.tcmv_create(B.make_desc(dtype="f32", layers=1, d=64, heads=1, mlp=64, patch=7))
+    assert B.tcmv_k_pad(B.make_desc(dtype="f32", layers=1, d=64, heads=1, mlp=64, patch=7)) == 148
+    B.tcmv_destroy(ctx)
+    assert B.tcmv_k_pad(B.make_desc(dtype="bf16", layers=1, d=64, heads=1, mlp=64, patch=14)) == 640
+    assert B.tcmv_k_pad(B.make_desc(dtype="bf16", layers=1, d=64, heads=1, mlp=64, patch=14, tpatch=2)) == 1216
+
+
+def _plan(desc, items):
+    enc = VisionEncoder(desc)
+    return enc, enc.plan(items, upload=False)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_plan_matches_reference_token_order(idx):
+    wl = workloads.small_config(idx)
+    enc, pl = _plan(wl.desc, wl.items)
+    grids = oe.grids_of(wl.items, wl.desc)
+    cu = oe.cu_seqlens_of(grids, wl.desc.use_cls)
+    assert pl.cu_seqlens == cu.tolist()
+    assert pl.info.n_tokens == cu[-1]
+    assert pl.info.n_patch_rows == sum(g[0] * g[1] * g[2] for g in grids)
+    assert pl.info.k == wl.desc.k and pl.info.k_pad % 2 == 0 and pl.info.k_pad >= wl.desc.k
+    thw = pl.row_map(0)
+    dst = pl.row_map(1)
+    ref = np.concatenate([op.token_coords(*g, wl.desc.merge) for g in grids if g[0]] or [np.zeros((0, 3), int)])
+    assert np.array_equal(thw >> 16, ref[:, 0]) and np.array_equal((thw >> 8) & 255, ref[:, 1])
+    assert np.array_equal(thw & 255, ref[:, 2])
+    # destination rows: patch rows in order, skipping one CLS row at the start of each segment
+    exp, r = [], 0
+    for g in grids:
+        n = g[0] * g[1] * g[2]
+        if n:
+            r += 1 if wl.desc.use_cls else 0
+            exp += list(range(r, r + n))
+            r += n
+    assert dst.tolist() == exp
+    pos = pl.row_map(2)
+    if wl.desc.pos == "sep2d":
+        assert np.array_equal(pos & 0xFFFF, ref[:, 1]) and np.array_equal(pos >> 16, ref[:, 2])
+    elif wl.desc.pos == "learned1d":
+        seg0 = np.searchsorted(cu, dst, side="right") - 1
+        assert np.array_equal(pos, dst - cu[seg0])
+    m2 = wl.desc.merge ** 2
+    assert pl.info.n_out_tokens == (cu[-1] // m2 if wl.desc.out_dim else 0)
+    assert pl.info.hidden_bytes == cu[-1] * wl.desc.d * 4
+
+
+def test_full_size_token_counts():
+    """Plan sizes of the five full workloads (no frames needed on the host)."""
+    expect = {1: 197, 2: 18432, 4: 32768}
+    for idx in (1, 2, 3, 4, 5):
+        wl = workloads.full_config(idx, with_frames=False, with_weights=False)
+        enc, pl = _plan(wl.desc, wl.items)
+        cu = oe.cu_seqlens_of(oe.grids_of(wl.items, wl.desc), wl.desc.use_cls)
+        assert pl.cu_seqlens == cu.tolist()
+        if idx in expect:
+            assert pl.info.n_tokens == expect[idx]
+        if idx == 5:
+            assert pl.info.n_segments == 26 and pl.info.n_items == 226
+            assert all(a == b for a, b in zip(pl.cu_seqlens[26:], pl.cu_seqlens[27:]))   # text: no tokens
+
+
+def test_bad_shapes_are_rejected():
+    desc = workloads.qwen_like_desc(layers=1, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
+    enc = VisionEncoder(desc)
+    I = workloads.Item
+    for bad in ([I(1, 1, 30, 28, 30, 28)],            # not a multiple of patch*merge
+                [I(1, 1, 28, 28, 0, 28)],             # empty target
+                [I(2, 3, 28, 28, 28, 28)],            # odd video length with temporal patch 2
+                [I(1, 1, 28, 28, 28 * 17, 28)],       # grid side above the position table
+                [I(1, 1, 0, 28, 28, 28)]):            # empty source
+        with pytest.raises(B.TcmvError) as e:
+            enc.plan(bad, upload=False)
+        assert e.value.code == B.TCMV_E_BAD_SHAPE, bad
+    with pytest.raises(B.TcmvError) as e:
+        enc.plan([I(7, 1, 28, 28, 28, 28)], upload=False)
+    assert e.value.code == B.TCMV_E_INVALID_ARG
+    # empty and text-only plans are valid and empty
+    for items in ([], [I(0, 0, 0, 0, 0, 0)] * 3):
+        pl = enc.plan(items, upload=False)
+        assert pl.info.n_tokens == 0 and pl.info.n_patch_rows == 0 and pl.cu_seqlens == [0] * (len(items) + 1)
+    # learned 1-D table too short
+    d2 = workloads.ModelDesc(dtype="bf16", layers=1, d=128, heads=2, mlp=128, patch=14, pos="learned1d", max_pos=3)
+    with pytest.raises(B.TcmvError) as e:
+        VisionEncoder(d2).plan([I(1, 1, 28, 28, 28, 28)], upload=False)
+    assert e.value.code == B.TCMV_E_BAD_SHAPE
+
+
+def test_device_calls_fail_cleanly_without_weights_or_gpu():
+    desc = workloads.qwen_like_desc(layers=1, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
+    enc = VisionEncoder(desc)
+    pl = enc.plan([workloads.Item(1, 1, 28, 28, 28, 28)], upload=False)
+    rc = B.lib().tcmv_encode(enc.ctx, pl.handle, 256, 256, 256, 1 << 30, None)
+    assert rc == B.TCMV_E_NO_WEIGHTS
+    rc = B.lib().tcmv_preprocess(enc.ctx, pl.handle, 256, None)     # item has a null frame pointer
+    assert rc == B.TCMV_E_INVALID_ARG
+    assert "frame pointer" in B.tcmv_last_error(enc.ctx)
+    assert B.tcmv_op_attention_workspace(B.TCMV_BF16, [0, 100, 100, 164], 128, 2) > 0

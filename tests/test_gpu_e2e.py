@@ -1,0 +1,150 @@
+"""GPU parity of the three stages (through the C ABI) against the CPU
+reference on reduced versions of the five workloads, plus the adversarial
+end-to-end variants (non-zero biases, random gamma/beta) they are built with.
+
+Tolerances.  Preprocessing and patch indexing: bit-exact.  fp32 model: 1e-4 of
+the row maximum.  bf16 model: per token max|err|/max|ref| <= 2e-2 and cosine
+>= 0.999 (the bar of the target), checked on every output row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from paper_2603_26498_amd import binding as B
+from paper_2603_26498_amd.runtime import VisionEncoder
+from util import assert_tokens_close
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(wl):
+    enc = VisionEncoder(wl.desc, wl.weights)
+    pl = enc.plan(wl.items)
+    patches = enc.preprocess(pl)
+    hidden = enc.encode(pl, patches)
+    out = enc.merge_project(pl, hidden) if wl.desc.out_dim else None
+    torch.cuda.synchronize()
+    return enc, pl, patches, hidden, out
+
+
+def check_patches(wl, ref, patches):
+    k = wl.desc.k
+    got = patches.float().cpu().numpy()
+    exp = np.concatenate([p for p in ref["patches"]], 0) if got.shape[0] else np.zeros((0, k), np.float32)
+    assert got.shape[0] == exp.shape[0]
+    assert np.array_equal(got[:, :k].view(np.uint32), exp.view(np.uint32)), "patches differ (must be bit-exact)"
+    assert not got[:, k:].any(), "padding columns must be zero"
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("affine", [False, True])
+def test_small_workloads(idx, affine):
+    wl = workloads.small_config(idx, random_affine=affine)
+    ref = oracle.run(wl)
+    enc, pl, patches, hidden, out = run_gpu(wl)
+    assert pl.cu_seqlens == ref["cu_seqlens"].tolist()
+    check_patches(wl, ref, patches)
+    rel, cos = (1e-4, 0.999999) if wl.desc.dtype == "f32" else (2e-2, 0.999)
+    assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], rel, cos, f"small{idx} hidden")
+    if out is not None:
+        assert_tokens_close(out.float().cpu().numpy(), ref["out"], rel, cos, f"small{idx} out")
+
+
+def test_resize_paths_bit_exact_many_sizes():
+    """Up- and down-scaling, odd source sizes, several items per launch."""
+    desc = workloads.ModelDesc(dtype="bf16", layers=0, d=128, heads=2, mlp=128, patch=14, tpatch=2, merge=2)
+    rng = np.random.default_rng(77)
+    items = []
+    for (n, sh, sw, dh, dw) in [(1, 37, 53, 28, 56), (2, 240, 426, 56, 84), (1, 31, 17, 84, 140), (4, 5, 1, 28, 28),
+                                (1, 1080, 1920, 224, 448), (1, 56, 56, 56, 56), (2, 100, 100, 112, 28)]:
+        items.append(workloads.Item(2 if n > 1 else 1, n, sh, sw, dh, dw, workloads.random_frames(rng, n, sh, sw)))
+    wl = workloads.Workload("resize", desc, items, workloads.make_weights(desc, 1))
+    enc = VisionEncoder(desc, wl.weights)
+    pl = enc.plan(items)
+    patches = enc.preprocess(pl)
+    torch.cuda.synchronize()
+    ref = oracle.run(wl, stages=("preprocess",))
+    check_patches(wl, ref, patches)
+
+
+@pytest.mark.parametrize("dtype,patch,tpatch,merge", [("f32", 16, 1, 1), ("f32", 7, 3, 1), ("bf16", 14, 1, 1),
+                                                      ("bf16", 8, 2, 2), ("f32", 14, 2, 2)])
+def test_preprocess_layouts_and_general_normalisation(dtype, patch, tpatch, merge):
+    mean = tuple(float(np.float32(m)) for m in (0.485, 0.456, 0.406))
+    std = tuple(float(np.float32(s)) for s in (0.229, 0.224, 0.225))
+    desc = workloads.ModelDesc(dtype=dtype, layers=0, d=128, heads=2, mlp=128, patch=patch, tpatch=tpatch, merge=merge,
+                               mean=mean, std=std)
+    rng = np.random.default_rng(5)
+    pm = patch * merge
+    items = [workloads.Item(1, 1, 3 * pm, 2 * pm, 3 * pm, 2 * pm, workloads.random_frames(rng, 1, 3 * pm, 2 * pm)),
+             workloads.Item(0, 0, 0, 0, 0, 0, None),
+             workloads.Item(2, 2 * tpatch, pm, 4 * pm, pm, 4 * pm, workloads.random_frames(rng, 2 * tpatch, pm, 4 * pm))]
+    wl = workloads.Workload("layout", desc, items, workloads.make_weights(desc, 1))
+    enc = VisionEncoder(desc, wl.weights)
+    pl = enc.plan(items)
+    patches = enc.preprocess(pl)
+    torch.cuda.synchronize()
+    check_patches(wl, oracle.run(wl, stages=("preprocess",)), patches)
+
+
+def test_text_only_and_empty_batches_launch_nothing():
+    wl = workloads.small_config(5)
+    enc = VisionEncoder(wl.desc, wl.weights)
+    for items in ([], [workloads.Item(0, 0, 0, 0, 0, 0, None)] * 4):
+        pl = enc.plan(items)
+        p = enc.preprocess(pl)
+        h = enc.encode(pl, p)
+        o = enc.merge_project(pl, h)
+        torch.cuda.synchronize()
+        assert p.shape[0] == 0 and h.shape[0] == 0 and o.shape[0] == 0
+
+
+def test_text_requests_do_not_disturb_other_requests():
+    wl = workloads.small_config(5)
+    only_visual = [it for it in wl.items if it.n_frames > 0]
+    enc = VisionEncoder(wl.desc, wl.weights)
+    res = []
+    for items in (wl.items, only_visual):
+        pl = enc.plan(items)
+        h = enc.encode(pl, enc.preprocess(pl))
+        res.append(enc.merge_project(pl, h).float().cpu().numpy())
+    assert np.array_equal(res[0], res[1])
+
+
+def test_permutation_equivariance_without_positions():
+    """Permuting the patch rows of a segment permutes the encoder output rows."""
+    desc = workloads.ModelDesc(dtype="bf16", layers=2, d=128, heads=2, mlp=256, patch=14, tpatch=1, merge=1)
+    w = workloads.make_weights(desc, 3, random_affine=True)
+    rng = np.random.default_rng(3)
+    it = workloads.Item(1, 1, 70, 84, 70, 84, workloads.random_frames(rng, 1, 70, 84))
+    enc = VisionEncoder(desc, w)
+    pl = enc.plan([it])
+    patches = enc.preprocess(pl)
+    perm = torch.from_numpy(rng.permutation(patches.shape[0])).to(patches.device)
+    a = enc.encode(pl, patches).clone()
+    b = enc.encode(pl, patches[perm].contiguous())
+    torch.cuda.synchronize()
+    assert_tokens_close(b.cpu().numpy(), a[perm].cpu().numpy(), 2e-2, 0.999, "permutation")
+
+
+def test_workspace_too_small_and_missing_projector_are_reported():
+    wl = workloads.small_config(2)
+    enc = VisionEncoder(wl.desc, wl.weights)
+    pl = enc.plan(wl.items)
+    patches = enc.preprocess(pl)
+    small = enc.workspace(256)
+    hidden = torch.empty((pl.info.n_tokens, wl.desc.d), device="cuda:0")
+    with pytest.raises(B.TcmvError) as e:
+        B.tcmv_encode(enc.ctx, pl.handle, patches, hidden, small, small.numel())
+    assert e.value.code == B.TCMV_E_WORKSPACE_TOO_SMALL
+    with pytest.raises(B.TcmvError) as e:
+        B.tcmv_merge_project(enc.ctx, pl.handle, hidden, hidden, small, small.numel())
+    assert e.value.code == B.TCMV_E_UNSUPPORTED
+
+
+def test_results_are_deterministic_run_to_run():
+    wl = workloads.small_config(3)
+    a = run_gpu(wl)[4].float().cpu().numpy()
+    b = run_gpu(wl)[4].float().cpu().numpy()
+    assert np.array_equal(a, b)

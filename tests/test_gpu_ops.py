@@ -1,0 +1,201 @@
+"""GPU parity of the single operators (called through the C ABI) against the
+CPU reference, with adversarial inputs that the end-to-end configurations
+cannot see: non-zero biases, ragged shapes, peaked softmax, segment leaks."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoder as oe
+from paper_2603_26498_amd import binding as B
+from util import assert_tokens_close, bf16_grid
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t.to(dtype) if dtype is not None else t
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- LayerNorm
+@pytest.mark.parametrize("rows,d", [(1, 256), (7, 160), (197, 256), (1030, 1280), (513, 1024), (33, 2048), (5, 64)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layernorm(rows, d, dtype):
+    rng = np.random.default_rng(rows * 7 + d)
+    x = (rng.normal(0, 3, (rows, d)) + rng.normal(0, 2, (rows, 1))).astype(np.float32)
+    g = (1 + rng.normal(0, 0.3, d)).astype(np.float32)
+    b = rng.normal(0, 0.2, d).astype(np.float32)
+    ref = oe.layernorm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-6)
+    y = torch.empty((rows, d), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
+    B.tcmv_op_layernorm(B.TCMV_BF16 if dtype == "bf16" else B.TCMV_F32, dev(x), dev(g), dev(b), y, rows, d, 1e-6)
+    sync()
+    got = y.float().cpu().numpy()
+    if dtype == "f32":
+        assert np.abs(got - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max())
+    else:
+        assert np.abs(got - ref).max() <= 2 ** -8 * np.abs(ref).max() + 1e-6
+        assert_tokens_close(got, ref, 1e-2, 0.9999, "layernorm")
+
+
+def test_layernorm_in_place_f32():
+    rng = np.random.default_rng(3)
+    x = rng.normal(0, 1, (37, 256)).astype(np.float32)
+    ref = oe.layernorm(x.astype(np.float64), np.ones(256), np.zeros(256), 1e-6)
+    t = dev(x)
+    B.tcmv_op_layernorm(B.TCMV_F32, t, dev(np.ones(256, np.float32)), dev(np.zeros(256, np.float32)), t, 37, 256, 1e-6)
+    sync()
+    assert np.abs(t.cpu().numpy() - ref).max() <= 2e-5
+
+
+# ---------------------------------------------------------------- GEMM
+def _gemm_ref(a, w, bias, epi, c0):
+    y = a.astype(np.float64) @ w.astype(np.float64).T + (bias.astype(np.float64) if bias is not None else 0)
+    if epi == B.EPI_GELU:
+        y = oe.gelu(y)
+    if epi == B.EPI_RESID:
+        y = c0.astype(np.float64) + y
+    return y
+
+
+@pytest.mark.parametrize("m,n,k", [(1, 64, 64), (127, 128, 64), (128, 128, 128), (300, 320, 640), (1000, 1280, 1216),
+                                   (257, 136, 192), (129, 3840, 1280), (2050, 1280, 5120)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_GELU, B.EPI_RESID])
+def test_gemm_bf16(m, n, k, epi):
+    rng = np.random.default_rng(m + 3 * n + 7 * k + epi)
+    a = bf16_grid(rng.normal(0, 1, (m, k)))
+    w = bf16_grid(rng.normal(0, 0.05, (n, k)))
+    bias = rng.normal(0, 0.5, n).astype(np.float32)
+    c0 = rng.normal(0, 1, (m, n)).astype(np.float32)
+    ref = _gemm_ref(a, w, bias, epi, c0)
+    if epi == B.EPI_RESID:
+        c = dev(c0)
+    else:
+        c = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.tcmv_op_gemm(B.TCMV_BF16, epi, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+    sync()
+    got = c.float().cpu().numpy()
+    if epi == B.EPI_RESID:      # fp32 output: only accumulation-order error
+        assert np.abs(got - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max())
+    else:
+        assert np.abs(got - ref).max() <= 2 ** -8 * np.abs(ref).max() + 1e-5
+        assert_tokens_close(got, ref, 1e-2, 0.9999, "gemm")
+
+
+def test_gemm_bf16_no_bias_and_exact_small_integers():
+    """Small integer inputs make every product and sum exact: bit-exact result expected."""
+    rng = np.random.default_rng(0)
+    m, n, k = 200, 192, 128
+    a = rng.integers(-3, 4, (m, k)).astype(np.float32)
+    w = rng.integers(-3, 4, (n, k)).astype(np.float32)
+    c = dev(np.zeros((m, n), np.float32))
+    B.tcmv_op_gemm(B.TCMV_BF16, B.EPI_RESID, dev(a, torch.bfloat16), dev(w, torch.bfloat16), None, c, m, n, k)
+    sync()
+    assert np.array_equal(c.cpu().numpy(), a @ w.T)
+
+
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (197, 256, 768), (70, 100, 50), (197, 1024, 256), (65, 64, 147)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_GELU, B.EPI_RESID])
+def test_gemm_f32(m, n, k, epi):
+    rng = np.random.default_rng(m + n + k + epi)
+    a = rng.normal(0, 1, (m, k)).astype(np.float32)
+    w = rng.normal(0, 0.1, (n, k)).astype(np.float32)
+    bias = rng.normal(0, 0.5, n).astype(np.float32)
+    c0 = rng.normal(0, 1, (m, n)).astype(np.float32)
+    ref = _gemm_ref(a, w, bias, epi, c0)
+    c = dev(c0) if epi == B.EPI_RESID else torch.full((m, n), float("nan"), device=DEV)
+    B.tcmv_op_gemm(B.TCMV_F32, epi, dev(a), dev(w), dev(bias), c, m, n, k)
+    sync()
+    assert np.abs(c.cpu().numpy() - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max())
+
+
+# ---------------------------------------------------------------- attention
+def _attn(dtype, qkv, cu, d, heads):
+    T = qkv.shape[0]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    cd = B.TCMV_BF16 if dtype == "bf16" else B.TCMV_F32
+    ws_bytes = B.tcmv_op_attention_workspace(cd, cu, d, heads)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)                                   # poison: padding must never be used
+    out = torch.full((T, d), float("nan"), dtype=tdt, device=DEV)
+    B.tcmv_op_attention(cd, dev(qkv, tdt), cu, d, heads, out, ws, ws.numel())
+    sync()
+    return out.float().cpu().numpy()
+
+
+def _qkv(rng, T, d, q_scale, dtype):
+    q = rng.normal(0, q_scale, (T, d)); k = rng.normal(0, 1, (T, d)); v = rng.normal(0, 1, (T, d))
+    x = np.concatenate([q, k, v], 1).astype(np.float32)
+    return bf16_grid(x) if dtype == "bf16" else x
+
+
+ATTN_CASES = [
+    # (segment lengths, d, heads, std of q): scores have std ~ q_scale
+    ([64], 64, 1, 1.0),
+    ([1], 128, 2, 1.0),                                 # single key: output = V
+    ([130, 0, 5, 257], 160, 2, 1.0),                    # ragged, empty segment, head size 80
+    ([576, 576], 128, 2, 0.3),                          # near-uniform softmax
+    ([300, 77, 1, 640], 160, 2, 6.0),                   # peaked softmax
+    ([1000], 320, 4, 8.0),                              # peaked, several query tiles and heads
+    ([63, 65, 127, 129], 64, 2, 4.0),
+    ([200], 96, 1, 2.0),
+    ([333], 32, 1, 2.0),
+]
+
+
+@pytest.mark.parametrize("lens,d,heads,qs", ATTN_CASES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention(lens, d, heads, qs, dtype):
+    rng = np.random.default_rng(sum(lens) + d + heads)
+    cu = [0] + list(np.cumsum(lens))
+    T = cu[-1]
+    qkv = _qkv(rng, T, d, qs, dtype)
+    x = qkv.astype(np.float64)
+    ref = oe.attention(x[:, :d], x[:, d:2 * d], x[:, 2 * d:], cu, heads)
+    got = _attn(dtype, qkv, [int(c) for c in cu], d, heads)
+    if dtype == "f32":
+        assert np.abs(got - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max())
+    else:
+        # probabilities and outputs are rounded to bf16 (2^-9 relative each)
+        assert np.abs(got - ref).max() <= 1.2e-2 * np.abs(ref).max()
+        assert_tokens_close(got, ref, 2e-2, 0.9995, "attention")
+        assert np.sqrt(((got - ref) ** 2).mean()) <= 4e-3 * np.sqrt((ref ** 2).mean())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_segments_do_not_leak(dtype):
+    """Encode {A, B} together == A and B alone; huge values in B must not move A."""
+    rng = np.random.default_rng(42)
+    d, heads = 160, 2
+    la, lb = 150, 90
+    qkv = _qkv(rng, la + lb, d, 2.0, dtype)
+    both = _attn(dtype, qkv, [0, la, la + lb], d, heads)
+    a_alone = _attn(dtype, qkv[:la], [0, la], d, heads)
+    b_alone = _attn(dtype, qkv[la:], [0, lb], d, heads)
+    assert np.array_equal(both[:la], a_alone) and np.array_equal(both[la:], b_alone)
+    poisoned = qkv.copy()
+    poisoned[la:, 2 * d:] = 3e4            # V of segment B
+    poisoned[la:, d:2 * d] *= 50           # K of segment B
+    got = _attn(dtype, poisoned, [0, la, la + lb], d, heads)
+    assert np.array_equal(got[:la], both[:la])
+
+
+def test_attention_zero_queries_give_mean_of_values():
+    rng = np.random.default_rng(9)
+    d, heads, T = 160, 2, 200
+    qkv = _qkv(rng, T, d, 1.0, "bf16")
+    qkv[:, :d] = 0
+    got = _attn("bf16", qkv, [0, T], d, heads)
+    ref = qkv[:, 2 * d:].astype(np.float64).mean(0, keepdims=True)
+    assert np.abs(got - ref).max() <= 1e-2 * np.abs(qkv[:, 2 * d:]).max()
+
+
+def test_empty_inputs_are_no_ops():
+    B.tcmv_op_layernorm(B.TCMV_BF16, None, None, None, None, 0, 256, 1e-6)
+    B.tcmv_op_gemm(B.TCMV_BF16, 0, None, None, None, None, 0, 128, 64)
+    B.tcmv_op_attention(B.TCMV_BF16, None, [0, 0, 0], 128, 2, None, None, 0)
+    sync()

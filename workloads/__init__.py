@@ -258,13 +258,13 @@ def small_config(idx: int, random_affine=True) -> Workload:
         wl = Workload("small2", desc, [Item(IMAGE, 1, 168, 168, 168, 168, random_frames(rng, 1, 168, 168))
                                        for _ in range(3)])
     elif idx == 3:
-        desc = qwen_like_desc(layers=2, d=160, heads=2, mlp=640, out_dim=192, max_grid=16)
+        desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
         wl = config3(n_images=5, lo=56, hi=224, desc=desc)
     elif idx == 4:
-        desc = qwen_like_desc(layers=2, d=160, heads=2, mlp=640, out_dim=192, max_grid=16)
+        desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
         wl = config4(n_frames=6, side=168, desc=desc)
     elif idx == 5:
-        desc = qwen_like_desc(layers=2, d=160, heads=2, mlp=640, out_dim=192, max_grid=16)
+        desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
         wl = config5(n_videos=1, n_images=3, n_text=4, video_frames=4, video_side=112, lo=56, hi=196,
                      src_lo=60, src_hi=200, desc=desc)
     else:
