@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the vision hot path on one MI355X.
+
+A "step" is one pass of the whole path (preprocess -> encode -> merge/project)
+over one batch of synthetic requests whose raw uint8 frames are already
+resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu]
+
+The default workload is the video configuration (one 64-frame 448x448 video,
+32768 encoder tokens, full bidirectional attention), which is the one the
+throughput target is quoted on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def algorithmic_flops(desc, cu, n_patch_rows):
+    """2*M*N*K counting, unpadded, no work for masked-out cross-segment scores."""
+    T = int(cu[-1])
+    seg = np.diff(np.asarray(cu, dtype=np.float64))
+    d, F, L = desc.d, desc.mlp, desc.layers
+    fl = {}
+    fl["embed_gemm"] = 2.0 * n_patch_rows * desc.k * d
+    fl["qkv_gemm"] = L * 2.0 * T * d * 3 * d
+    fl["out_gemm"] = L * 2.0 * T * d * d
+    fl["fc1_gemm"] = L * 2.0 * T * d * F
+    fl["fc2_gemm"] = L * 2.0 * T * d * F
+    fl["attention"] = L * 4.0 * float((seg ** 2).sum()) * d
+    if desc.out_dim:
+        m2 = desc.merge ** 2
+        fl["merge_gemm"] = 2.0 * (T / m2) * ((m2 * d) ** 2 + m2 * d * desc.out_dim)
+    else:
+        fl["merge_gemm"] = 0.0
+    return fl
+
+
+def algorithmic_bytes(desc, items, cu, n_patch_rows):
+    """HBM bytes the bandwidth-bound kernels must move (read sources once, write results once)."""
+    T = int(cu[-1])
+    e = 2 if desc.dtype == "bf16" else 4
+    src = sum(3 * it.src_h * it.src_w * it.n_frames for it in items)
+    n_ln = 2 * desc.layers + (1 if desc.final_ln else 0) + (1 if desc.out_dim else 0)
+    return {"preprocess": float(src + n_patch_rows * desc.k * e),
+            "layernorm": float(n_ln * T * desc.d * (4 + e))}
+
+
+def cpu_baseline(wl, cu, n_patch_rows, budget_note=True):
+    """Times the CPU reference (as it is, float64) on a bounded sample of the same
+    workload and scales to the whole job: preprocessing + embedding of a few
+    frames, one encoder block with the dense parts on a row sample and the
+    attention of ONE head over every segment, the projector on a row sample."""
+    import oracle
+    from oracle import encoder as oe
+    from oracle import preprocess as op
+    desc, w = wl.desc, wl.weights
+    T = int(cu[-1])
+    dt = np.float64
+    rng = np.random.default_rng(0)
+    t_total = 0.0
+    parts = {}
+    # -- preprocess + embed: first visual item, at most 4 frames
+    vis = [it for it in wl.items if it.n_frames > 0]
+    it0 = vis[0]
+    nf = min(it0.n_frames, 2 * desc.tpatch) if it0.n_frames > 1 else 1
+    sample = workloads.Item(it0.modality, nf, it0.src_h, it0.src_w, it0.dst_h, it0.dst_w, it0.frames[:nf])
+    t0 = time.perf_counter()
+    p = op.preprocess_item(sample, desc)
+    t_pre = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _ = p.astype(dt) @ w["w_pe"].astype(dt).T + w["b_pe"].astype(dt)
+    t_emb = time.perf_counter() - t0
+    scale_rows = n_patch_rows / p.shape[0]
+    parts["preprocess_s"] = t_pre * scale_rows
+    parts["embed_s"] = t_emb * scale_rows
+    # -- one block: dense parts on a row sample
+    rs = min(T, 8192)
+    x = rng.normal(0, 1, (rs, desc.d))
+    g = lambda n: w["l0." + n].astype(dt)
+    t0 = time.perf_counter()
+    h = oe.layernorm(x, g("ln1_g"), g("ln1_b"), desc.ln_eps)
+    qkv = h @ g("w_qkv").T + g("b_qkv")
+    x = x + (qkv[:, :desc.d] @ g("w_o").T + g("b_o"))
+    h = oe.layernorm(x, g("ln2_g"), g("ln2_b"), desc.ln_eps)
+    h = oe.gelu(h @ g("w_1").T + g("b_1"))
+    x = x + (h @ g("w_2").T + g("b_2"))
+    t_dense = (time.perf_counter() - t0) * (T / rs)
+    # -- attention: one head over all segments (every head has the same shape)
+    dh = desc.d // desc.heads
+    q1, k1, v1 = (rng.normal(0, 1, (T, dh)) for _ in range(3))
+    t0 = time.perf_counter()
+    oe.attention(q1, k1, v1, cu, 1)
+    t_attn = (time.perf_counter() - t0) * desc.heads
+    parts["block_dense_s"] = t_dense
+    parts["block_attention_s"] = t_attn
+    t_merge = 0.0
+    if desc.out_dim:
+        m2 = desc.merge ** 2
+        rs2 = min(T, 4096)
+        t0 = time.perf_counter()
+        oe.merge_project(rng.normal(0, 1, (rs2, desc.d)), desc, w, dt)
+        t_merge = (time.perf_counter() - t0) * (T / rs2)
+    parts["merge_s"] = t_merge
+    t_total = parts["preprocess_s"] + parts["embed_s"] + desc.layers * (t_dense + t_attn) + t_merge
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {"value": T / t_total, "unit": "visual tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"float64 numpy reference; preprocess+embed of {nf} frame(s) of the first request, one "
+                       f"encoder block (dense parts on {rs} of {T} rows, attention of 1 of {desc.heads} heads over "
+                       f"all segments), projector on {min(T, 4096)} rows; scaled to {desc.layers} layers and the "
+                       f"whole batch; estimated whole-job time {t_total:.1f} s"),
+            "parts_s": {k: round(v, 3) for k, v in parts.items()}, "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--layers", type=int, default=None, help="override depth (not a valid headline number)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-reference timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_26498_amd import binding as B
+    from paper_2603_26498_amd.runtime import VisionEncoder
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the vision path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    wl = workloads.full_config(args.config, layers=args.layers)
+    desc = wl.desc
+    enc = VisionEncoder(desc, wl.weights)
+    plan = enc.plan(wl.items)                 # raw frames are uploaded here: resident in HBM before timing
+    info = plan.info
+    cu = plan.cu_seqlens
+    T, Tp = int(info.n_tokens), int(info.n_patch_rows)
+    n_frames = sum(it.n_frames for it in wl.items)
+    bf16 = desc.dtype == "bf16"
+    patches = torch.empty((Tp, info.k_pad), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda:0")
+    hidden = torch.empty((T, desc.d), dtype=torch.float32, device="cuda:0")
+    out = torch.empty((int(info.n_out_tokens), max(desc.out_dim, 1)), dtype=torch.bfloat16 if bf16 else torch.float32,
+                      device="cuda:0")
+    ws = enc.workspace(max(info.encode_workspace_bytes, info.merge_workspace_bytes))
+    stream = torch.cuda.current_stream()
+    sp = __import__("ctypes").c_void_p(stream.cuda_stream)
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def step(record=False):
+        if record: ev[0].record(stream)
+        B.tcmv_preprocess(enc.ctx, plan.handle, patches, sp)
+        if record: ev[1].record(stream)
+        B.tcmv_encode(enc.ctx, plan.handle, patches, hidden, ws, ws.numel(), sp)
+        if record: ev[2].record(stream)
+        if desc.out_dim:
+            B.tcmv_merge_project(enc.ctx, plan.handle, hidden, out, ws, ws.numel(), sp)
+        if record: ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.tcmv_profile_enable(enc.ctx, 1)
+    B.tcmv_profile_read(enc.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(record=(i == args.steps - 1))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.tcmv_profile_read(enc.ctx)
+    B.tcmv_profile_enable(enc.ctx, 0)
+    stage_ms = {"preprocess": ev[0].elapsed_time(ev[1]), "encode": ev[1].elapsed_time(ev[2]),
+                "merge_project": ev[2].elapsed_time(ev[3])}
+
+    ms_per_step = elapsed / args.steps * 1e3
+    fl = algorithmic_flops(desc, cu, Tp)
+    by = algorithmic_bytes(desc, wl.items, cu, Tp)
+    total_flops = sum(fl.values())
+    kern = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        per_step_ms = ms / args.steps
+        e = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": cnt // args.steps,
+             "avg_launch_us": round(ms / cnt * 1e3, 2)}
+        if name in fl and fl[name] > 0:
+            e["tflops"] = round(fl[name] / (per_step_ms * 1e-3) / 1e12, 2)
+            e["frac_of_bf16_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        if name in by:
+            e["gbs"] = round(by[name] / (per_step_ms * 1e-3) / 1e9, 1)
+            e["frac_of_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        kern[name] = e
+    # dominant kernel = the kernel class with the most time per step
+    dom = max(kern, key=lambda n: kern[n]["ms_per_step"])
+    ms_dom, cnt_dom = prof[dom]
+    avg_s = ms_dom / cnt_dom * 1e-3
+    if dom in fl and fl[dom] > 0:
+        per_launch = fl[dom] / (cnt_dom / args.steps)
+        roof = {"kernel": dom, "bound": "mfma", "achieved": round(per_launch / avg_s / 1e12, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "traffic": None}
+    else:
+        per_launch = by[dom] / (cnt_dom / args.steps)
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(per_launch / avg_s / 1e9, 1),
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None}
+    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+    roof["avg_launch_us"] = round(avg_s * 1e6, 2)
+    roof["algorithmic_per_launch"] = per_launch
+
+    enc_merge_ms = stage_ms["encode"] + stage_ms["merge_project"]
+    res = {
+        "metric": "visual tokens/sec encoded (ViT fwd bf16) + % of MI355X bf16 MFMA peak",
+        "value": round(T / (ms_per_step * 1e-3), 1),
+        "unit": "visual tokens/s (encoder tokens, before the 2x2 merge)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "config_index": args.config, "requests": len(wl.items),
+                   "frames": n_frames, "encoder_tokens": T, "merged_tokens": int(info.n_out_tokens),
+                   "layers": desc.layers, "d": desc.d, "heads": desc.heads, "mlp": desc.mlp,
+                   "out_dim": desc.out_dim, "headline": args.layers is None},
+        "frames_per_s": round(n_frames / (ms_per_step * 1e-3), 1),
+        "merged_tokens_per_s": round(int(info.n_out_tokens) / (ms_per_step * 1e-3), 1),
+        "algorithmic_tflop_per_step": round(total_flops / 1e12, 3),
+        "gemm_attention_tflops": round(total_flops / (enc_merge_ms * 1e-3) / 1e12, 2),
+        "mfma_peak_frac": round(total_flops / (enc_merge_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "stage_ms": {k: round(v, 3) for k, v in stage_ms.items()},
+        "kernels": kern,
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(wl, cu, Tp)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

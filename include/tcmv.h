@@ -187,6 +187,19 @@ int tcmv_encode(tcmv_ctx *ctx, tcmv_plan *plan, const void *d_patches, void *d_h
 int tcmv_merge_project(tcmv_ctx *ctx, tcmv_plan *plan, const void *d_hidden, void *d_out,
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
+/* ---- per-kernel timing ------------------------------------------------------
+ * When enabled, the three stage calls bracket every kernel launch with a pair of
+ * HIP events on the caller's stream (host-side objects, no device memory).
+ * tcmv_profile_read waits for the recorded events, adds the elapsed
+ * milliseconds and launch counts per kernel class to ms[] / launches[] (arrays
+ * of TCMV_K_COUNT entries, overwritten) and forgets the events. */
+enum {
+  TCMV_K_PREPROCESS = 0, TCMV_K_EMBED_GEMM, TCMV_K_LAYERNORM, TCMV_K_QKV_GEMM, TCMV_K_ATTENTION,
+  TCMV_K_OUT_GEMM, TCMV_K_FC1_GEMM, TCMV_K_FC2_GEMM, TCMV_K_MERGE_GEMM, TCMV_K_OTHER, TCMV_K_COUNT
+};
+int tcmv_profile_enable(tcmv_ctx *ctx, int on);
+int tcmv_profile_read(tcmv_ctx *ctx, double *ms, int64_t *launches);
+
 /* ---- single operators (the kernels the stages are built from), exposed so
  * that each can be checked and timed alone.  All pointers are device pointers.
  * dtype selects the bf16 MFMA path or the fp32 path. ---------------------- */

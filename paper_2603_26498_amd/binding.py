@@ -71,6 +71,8 @@ SIGNATURES = {
     "tcmv_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tcmv_merge_project": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                      C.c_void_p]),
+    "tcmv_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "tcmv_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "tcmv_op_layernorm": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                     C.c_float, C.c_void_p]),
     "tcmv_op_gemm": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
@@ -213,6 +215,23 @@ def tcmv_encode(ctx, plan, d_patches, d_hidden, d_workspace, workspace_bytes, st
 def tcmv_merge_project(ctx, plan, d_hidden, d_out, d_workspace, workspace_bytes, stream=None):
     _check(ctx, lib().tcmv_merge_project(ctx, plan, _ptr(d_hidden), _ptr(d_out), _ptr(d_workspace), workspace_bytes,
                                          stream), "tcmv_merge_project")
+
+
+KERNEL_CLASSES = ("preprocess", "embed_gemm", "layernorm", "qkv_gemm", "attention", "out_gemm", "fc1_gemm",
+                  "fc2_gemm", "merge_gemm", "other")
+
+
+def tcmv_profile_enable(ctx, on):
+    _check(ctx, lib().tcmv_profile_enable(ctx, int(on)), "tcmv_profile_enable")
+
+
+def tcmv_profile_read(ctx):
+    """-> {kernel class: (milliseconds, launches)} since the last read."""
+    n = len(KERNEL_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(ctx, lib().tcmv_profile_read(ctx, ms, cnt), "tcmv_profile_read")
+    return {KERNEL_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}
 
 
 def tcmv_op_layernorm(dtype, d_x, d_gamma, d_beta, d_y, rows, d, eps, stream=None):

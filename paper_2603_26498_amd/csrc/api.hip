@@ -21,6 +21,11 @@ struct tcmv_ctx {
   tcmv_weights w;
   std::vector<const void*> layer;   // layers*12 device pointers (copied)
   std::string err;
+  // per-kernel timing
+  bool profiling = false;
+  struct Span { hipEvent_t a, b; int cat; };
+  std::vector<Span> spans;          // recorded, not yet read
+  std::vector<Span> free_spans;     // event pairs ready for reuse
 };
 
 struct tcmv_plan {
@@ -180,6 +185,29 @@ void build_work(std::vector<AttnWork>& work, const std::vector<int64_t>& seg_sta
   std::stable_sort(work.begin(), work.end(), [](const AttnWork& a, const AttnWork& b) { return a.seg_len > b.seg_len; });
 }
 
+// Runs `launch` and, when timing is on, brackets it with an event pair.
+template <class F>
+hipError_t timed(tcmv_ctx* ctx, int cat, hipStream_t s, F&& launch) {
+  if (!ctx->profiling) return launch();
+  tcmv_ctx::Span sp{};
+  if (!ctx->free_spans.empty()) {
+    sp = ctx->free_spans.back();
+    ctx->free_spans.pop_back();
+  } else {
+    hipError_t e = hipEventCreate(&sp.a);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&sp.b);
+    if (e != hipSuccess) { (void)hipEventDestroy(sp.a); return e; }
+  }
+  sp.cat = cat;
+  hipError_t e = hipEventRecord(sp.a, s);
+  if (e == hipSuccess) e = launch();
+  if (e == hipSuccess) e = hipEventRecord(sp.b, s);
+  if (e != hipSuccess) { ctx->free_spans.push_back(sp); return e; }
+  ctx->spans.push_back(sp);
+  return hipSuccess;
+}
+
 hipError_t run_gemm(const tcmv_ctx* ctx, const GemmArgs& g, hipStream_t s) {
   return ctx->desc.dtype == TCMV_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
 }
@@ -226,7 +254,34 @@ int tcmv_create(const tcmv_model_desc* desc, tcmv_ctx** out) {
   return TCMV_OK;
 }
 
-void tcmv_destroy(tcmv_ctx* ctx) { delete ctx; }
+void tcmv_destroy(tcmv_ctx* ctx) {
+  if (!ctx) return;
+  for (auto* v : {&ctx->spans, &ctx->free_spans})
+    for (auto& sp : *v) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  delete ctx;
+}
+
+int tcmv_profile_enable(tcmv_ctx* ctx, int on) {
+  if (!ctx) return TCMV_E_INVALID_ARG;
+  ctx->profiling = on != 0;
+  return TCMV_OK;
+}
+
+int tcmv_profile_read(tcmv_ctx* ctx, double* ms, int64_t* launches) {
+  if (!ctx || !ms || !launches) return TCMV_E_INVALID_ARG;
+  for (int i = 0; i < TCMV_K_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  int rc = TCMV_OK;
+  for (auto& sp : ctx->spans) {
+    hipError_t e = hipEventSynchronize(sp.b);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, sp.a, sp.b);
+    if (e != hipSuccess) rc = fail_hip(ctx, e, "profile read");
+    else { ms[sp.cat] += t; launches[sp.cat] += 1; }
+    ctx->free_spans.push_back(sp);
+  }
+  ctx->spans.clear();
+  return rc;
+}
 
 const char* tcmv_last_error(const tcmv_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
 
@@ -410,7 +465,7 @@ int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) 
   a.patch = ctx->desc.patch; a.tpatch = ctx->desc.tpatch;
   a.k = (int)ctx->k; a.k_pad = (int)ctx->k_pad;
   a.out_bf16 = ctx->desc.dtype == TCMV_BF16;
-  hipError_t e = launch_preprocess(a, (hipStream_t)stream);
+  hipError_t e = timed(ctx, TCMV_K_PREPROCESS, (hipStream_t)stream, [&] { return launch_preprocess(a, (hipStream_t)stream); });
   if (e != hipSuccess) return fail_hip(ctx, e, "preprocess launch");
   return TCMV_OK;
 }
@@ -450,24 +505,25 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
     g.dst_row = dev<int32_t>(p, p->off_prow_dst); g.pos_idx = dev<int32_t>(p, p->off_prow_pos);
     g.pos0 = reinterpret_cast<const float*>(ctx->w.pos0); g.pos1 = reinterpret_cast<const float*>(ctx->w.pos1);
     g.pos_kind = d.pos;
-    TCMV_CHECK(run_gemm(ctx, g, s), "patch-embed GEMM");
+    TCMV_CHECK(timed(ctx, TCMV_K_EMBED_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "patch-embed GEMM");
     if (d.use_cls)
-      TCMV_CHECK(launch_cls_rows(x, dev<int32_t>(p, p->off_cls), (int)p->cls_rows.size(),
-                                 reinterpret_cast<const float*>(ctx->w.cls),
-                                 d.pos == TCMV_POS_LEARNED_1D ? reinterpret_cast<const float*>(ctx->w.pos0) : nullptr,
-                                 d.d, s), "CLS rows");
+      TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
+                   return launch_cls_rows(x, dev<int32_t>(p, p->off_cls), (int)p->cls_rows.size(),
+                                          reinterpret_cast<const float*>(ctx->w.cls),
+                                          d.pos == TCMV_POS_LEARNED_1D ? reinterpret_cast<const float*>(ctx->w.pos0) : nullptr,
+                                          d.d, s); }), "CLS rows");
   }
   for (int l = 0; l < d.layers; ++l) {
     const void* const* L = ctx->layer.data() + (size_t)l * 12;
     auto f = [&](int j) { return reinterpret_cast<const float*>(L[j]); };
-    TCMV_CHECK(launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s), "LN1");
+    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s); }), "LN1");
     {
       GemmArgs g{};
       g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * d.d; g.k = d.d;
       g.c = qkv; g.epi = EPI_QKV;
       if (bf) { g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->t_vpad; g.vcol = dev<int32_t>(p, p->off_vcol); }
       else { g.ldc = 3 * d.d; }
-      TCMV_CHECK(run_gemm(ctx, g, s), "QKV GEMM");
+      TCMV_CHECK(timed(ctx, TCMV_K_QKV_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "QKV GEMM");
     }
     {
       AttnArgs a{};
@@ -477,37 +533,39 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
         a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->t_vpad;
         a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
-        TCMV_CHECK(launch_attn_bf16(a, s), "attention");
+        TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
       } else {
         const float* q3 = reinterpret_cast<const float*>(qkv);
         a.q = q3; a.k = q3 + d.d; a.ldqk = 3 * d.d; a.v = q3 + 2 * d.d; a.ldv = 3 * d.d;
         a.scale = (float)(1.0 / std::sqrt((double)dh));
-        TCMV_CHECK(launch_attn_f32(a, s), "attention");
+        TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_f32(a, s); }), "attention");
       }
     }
     {
       GemmArgs g{};
       g.a = xn; g.lda = d.d; g.w = L[4]; g.bias = f(5); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.d;
       g.epi = EPI_RESID;
-      TCMV_CHECK(run_gemm(ctx, g, s), "out-proj GEMM");
+      TCMV_CHECK(timed(ctx, TCMV_K_OUT_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "out-proj GEMM");
     }
-    TCMV_CHECK(launch_layernorm(x, f(6), f(7), xn, T, d.d, d.ln_eps, bf, s), "LN2");
+    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(6), f(7), xn, T, d.d, d.ln_eps, bf, s); }), "LN2");
     {
       GemmArgs g{};
       g.a = xn; g.lda = d.d; g.w = L[8]; g.bias = f(9); g.c = hbuf; g.ldc = d.mlp; g.m = T; g.n = d.mlp; g.k = d.d;
       g.epi = EPI_GELU;
-      TCMV_CHECK(run_gemm(ctx, g, s), "fc1 GEMM");
+      TCMV_CHECK(timed(ctx, TCMV_K_FC1_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "fc1 GEMM");
     }
     {
       GemmArgs g{};
       g.a = hbuf; g.lda = d.mlp; g.w = L[10]; g.bias = f(11); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.mlp;
       g.epi = EPI_RESID;
-      TCMV_CHECK(run_gemm(ctx, g, s), "fc2 GEMM");
+      TCMV_CHECK(timed(ctx, TCMV_K_FC2_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "fc2 GEMM");
     }
   }
   if (d.final_ln)
-    TCMV_CHECK(launch_layernorm(x, reinterpret_cast<const float*>(ctx->w.lnf_g), reinterpret_cast<const float*>(ctx->w.lnf_b),
-                                x, T, d.d, d.ln_eps, 0, s), "final LN");
+    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] {
+                 return launch_layernorm(x, reinterpret_cast<const float*>(ctx->w.lnf_g),
+                                         reinterpret_cast<const float*>(ctx->w.lnf_b), x, T, d.d, d.ln_eps, 0, s); }),
+               "final LN");
   return TCMV_OK;
 }
 
@@ -532,19 +590,21 @@ int tcmv_merge_project(tcmv_ctx* ctx, tcmv_plan* p, const void* d_hidden, void* 
   const int64_t T = p->n_tokens, Tm = T / m2;
   const int dm = d.d * m2;
   hipError_t e;
-  TCMV_CHECK(launch_layernorm(reinterpret_cast<const float*>(d_hidden), reinterpret_cast<const float*>(ctx->w.lnm_g),
-                              reinterpret_cast<const float*>(ctx->w.lnm_b), y, T, d.d, d.ln_eps, bf, s), "merger LN");
+  TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] {
+               return launch_layernorm(reinterpret_cast<const float*>(d_hidden), reinterpret_cast<const float*>(ctx->w.lnm_g),
+                                       reinterpret_cast<const float*>(ctx->w.lnm_b), y, T, d.d, d.ln_eps, bf, s); }),
+             "merger LN");
   {
     GemmArgs g{};
     g.a = y; g.lda = dm; g.w = ctx->w.w_m1; g.bias = reinterpret_cast<const float*>(ctx->w.b_m1);
     g.c = h; g.ldc = dm; g.m = Tm; g.n = dm; g.k = dm; g.epi = EPI_GELU;
-    TCMV_CHECK(run_gemm(ctx, g, s), "merger fc1 GEMM");
+    TCMV_CHECK(timed(ctx, TCMV_K_MERGE_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "merger fc1 GEMM");
   }
   {
     GemmArgs g{};
     g.a = h; g.lda = dm; g.w = ctx->w.w_m2; g.bias = reinterpret_cast<const float*>(ctx->w.b_m2);
     g.c = d_out; g.ldc = d.out_dim; g.m = Tm; g.n = d.out_dim; g.k = dm; g.epi = EPI_STORE;
-    TCMV_CHECK(run_gemm(ctx, g, s), "merger fc2 GEMM");
+    TCMV_CHECK(timed(ctx, TCMV_K_MERGE_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "merger fc2 GEMM");
   }
   return TCMV_OK;
 }
