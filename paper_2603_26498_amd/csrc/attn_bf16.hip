@@ -45,9 +45,15 @@ struct AttnCfg {
   static constexpr int V_BYTES = DHP * BKV * 2;
   static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int NCH_K = BKV * KCH, NCH_V = DH * (BKV / 8);
-  static constexpr int LK = (NCH_K + NTHREADS - 1) / NTHREADS, LV = (NCH_V + NTHREADS - 1) / NTHREADS;
+  static constexpr int NLOAD = (NCH_K + NCH_V) / NTHREADS;   // 16-byte global loads per thread per tile
+  static_assert((NCH_K + NCH_V) % NTHREADS == 0, "tile does not split evenly over the workgroup");
 };
 
+// V^T tile in LDS: row = head-dim index (128 bytes = 64 keys).  Inside a row the
+// keys are stored in the order the PV MFMA wants them: 16-byte chunk (2G + g)
+// holds keys {16G + 4g + 0..3, 16G + 8 + 4g + 0..3}, i.e. exactly the 8 keys a
+// lane of half-wave g contributes to k-step G.  Chunks are XOR-swizzled by the
+// row so that 32 lanes reading the same chunk of 32 different rows hit all banks.
 template <int DH>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
@@ -61,6 +67,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const AttnWork w = a.work[p - head * a.n_work];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __builtin_assume(tid >= 0 && tid < NTHREADS);
   const int lr = lane & 31, lg = lane >> 5;
   const uint16_t* Q = reinterpret_cast<const uint16_t*>(a.q);
   const uint16_t* K = reinterpret_cast<const uint16_t*>(a.k);
@@ -87,58 +94,58 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
-  uint4 rk[C::LK], rv[C::LV];
-  auto load_tile = [&](int j0, bool tail) {
+  // global -> register staging of one K / V^T tile: NLOAD 16-byte chunks per thread;
+  // chunk ids [0, NCH_K) are K, the rest V^T.  Source pointers and LDS offsets are
+  // selected arithmetically (no divergent control flow) and computed once.
+  uint4 rg[C::NLOAD];
+  const uint16_t* gsrc[C::NLOAD];   // source of tile 0; K advances by 64 rows, V^T by 64 columns per tile
+  int lds_lo[C::NLOAD], lds_hi[C::NLOAD];   // byte offsets of the two 8-byte halves inside a stage
+  int vkey0[C::NLOAD];              // V^T chunks: first key of the chunk inside the tile, K chunks: -1
+  int krow[C::NLOAD];               // K chunks: row inside the tile
 #pragma unroll
-    for (int i = 0; i < C::LK; ++i) {
-      const int c = tid + i * NTHREADS;
-      if (c < C::NCH_K) {
-        const int row = c / C::KCH, cc = c - row * C::KCH;
-        int64_t gr = (int64_t)w.seg_start + j0 + row;
-        if (gr >= a.t_total) gr = a.t_total - 1;
-        rk[i] = *reinterpret_cast<const uint4*>(K + (size_t)gr * a.ldqk + head * DH + cc * 8);
+  for (int i = 0; i < C::NLOAD; ++i) {
+    const int c = tid + i * NTHREADS;
+    const bool is_k = c < C::NCH_K;
+    const int rowk = c / C::KCH, cck = c - rowk * C::KCH;
+    const int cv = c - C::NCH_K;
+    const int rowv = cv >> 3, ccv = cv & 7;
+    const int G = ccv >> 1, h = ccv & 1, sw = rowv & 7;
+    const int vb = C::K_BYTES + rowv * (BKV * 2) + h * 8;
+    lds_lo[i] = is_k ? rowk * C::KSTR + cck * 16 : vb + (((2 * G) ^ sw) << 4);
+    lds_hi[i] = is_k ? rowk * C::KSTR + cck * 16 + 8 : vb + (((2 * G + 1) ^ sw) << 4);
+    vkey0[i] = is_k ? -1 : ccv * 8;
+    krow[i] = is_k ? rowk : 0;
+    const uint16_t* ks = K + (size_t)head * DH + (size_t)(w.seg_start + rowk) * a.ldqk + cck * 8;
+    const uint16_t* vs = VT + ((size_t)head * DH + rowv) * a.ldv + w.v0 + ccv * 8;
+    gsrc[i] = is_k ? ks : vs;
+  }
+  const int64_t kstep = (int64_t)BKV * a.ldqk;
+  auto load_tile = [&](int t, bool tail) {
+#pragma unroll
+    for (int i = 0; i < C::NLOAD; ++i) {
+      const bool is_k = vkey0[i] < 0;
+      const uint16_t* src = gsrc[i] + (is_k ? (int64_t)t * kstep : (int64_t)t * BKV);
+      if (tail && is_k) {   // last tile: rows past the end of the buffer are clamped (their scores are masked)
+        const int64_t over = (int64_t)w.seg_start + t * BKV + krow[i] - (a.t_total - 1);
+        if (over > 0) src -= over * a.ldqk;
       }
-    }
-#pragma unroll
-    for (int i = 0; i < C::LV; ++i) {
-      const int c = tid + i * NTHREADS;
-      if (c < C::NCH_V) {
-        const int row = c >> 3, cc = c & 7;
-        uint4 v = *reinterpret_cast<const uint4*>(VT + (size_t)(head * DH + row) * a.ldv + w.v0 + j0 + cc * 8);
-        if (tail) {   // keys beyond the segment: force exact zeros (the buffer may hold anything there)
-          const int valid = w.seg_len - (j0 + cc * 8);   // number of valid keys in this chunk
-          uint32_t* u = reinterpret_cast<uint32_t*>(&v);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (2 * e >= valid) u[e] = 0u;
-            else if (2 * e + 1 >= valid) u[e] &= 0xFFFFu;
-          }
-        }
-        rv[i] = v;
+      uint4 v = *reinterpret_cast<const uint4*>(src);
+      if (tail && !is_k) {  // keys beyond the segment: force exact zeros (the buffer may hold anything there)
+        const int valid = w.seg_len - (t * BKV + vkey0[i]);
+        v.x = (valid <= 0) ? 0u : (valid == 1 ? (v.x & 0xFFFFu) : v.x);
+        v.y = (valid <= 2) ? 0u : (valid == 3 ? (v.y & 0xFFFFu) : v.y);
+        v.z = (valid <= 4) ? 0u : (valid == 5 ? (v.z & 0xFFFFu) : v.z);
+        v.w = (valid <= 6) ? 0u : (valid == 7 ? (v.w & 0xFFFFu) : v.w);
       }
+      rg[i] = v;
     }
   };
   auto store_tile = [&](int buf) {
-    uint8_t* sk = smem + buf * C::STAGE;
-    uint8_t* sv = sk + C::K_BYTES;
+    uint8_t* st = smem + buf * C::STAGE;
 #pragma unroll
-    for (int i = 0; i < C::LK; ++i) {
-      const int c = tid + i * NTHREADS;
-      if (c < C::NCH_K) {
-        const int row = c / C::KCH, cc = c - row * C::KCH;
-        *reinterpret_cast<uint4*>(sk + row * C::KSTR + cc * 16) = rk[i];
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < C::LV; ++i) {
-      const int c = tid + i * NTHREADS;
-      if (c < C::NCH_V) {
-        const int row = c >> 3, cc = c & 7;
-        const int sw = row & 15;
-        uint8_t* base = sv + row * (BKV * 2);
-        *reinterpret_cast<uint2*>(base + (((2 * cc) ^ sw) << 3)) = make_uint2(rv[i].x, rv[i].y);
-        *reinterpret_cast<uint2*>(base + (((2 * cc + 1) ^ sw) << 3)) = make_uint2(rv[i].z, rv[i].w);
-      }
+    for (int i = 0; i < C::NLOAD; ++i) {
+      *reinterpret_cast<uint2*>(st + lds_lo[i]) = make_uint2(rg[i].x, rg[i].y);
+      *reinterpret_cast<uint2*>(st + lds_hi[i]) = make_uint2(rg[i].z, rg[i].w);
     }
   };
 
@@ -158,22 +165,41 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * BKV;
-    if (t + 1 < n_tiles) load_tile(j0 + BKV, ragged && (t + 2 == n_tiles));
+    if (t + 1 < n_tiles) load_tile(t + 1, ragged && (t + 2 == n_tiles));
     const uint8_t* sk = smem + (t & 1) * C::STAGE;
     const uint8_t* sv = sk + C::K_BYTES;
 
-    // ---- S^T tile: 64 keys x 32 queries
+    // ---- S^T tile: 64 keys x 32 queries.  All K fragments are requested first so
+    // that the LDS latency overlaps; the two key blocks alternate on the MFMA pipe.
+    bf16x8 kf[2][C::KS];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        kf[kb][ks] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
     f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+    for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[ks], s[kb], 0, 0, 0);
+
+    // V^T fragments of the first two k-steps are requested before the softmax arithmetic
+    bf16x8 vf[C::MT][4];
+    auto load_vf = [&](int G) {
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        const int row = mt * 32 + lr;
+        vf[mt][G] = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * G + lg) ^ (row & 7)) << 4));
       }
-    }
+    };
+    load_vf(0);
+    load_vf(1);
+
     if (ragged && t + 1 == n_tiles) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -194,7 +220,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cs);
     m_run = m_new;
     const float mc = m_new * cs;
-    bf16x8 pf[2][2];
+    bf16x8 pf[4];     // pf[G]: keys of k-step G = 2*kb + j
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -209,7 +235,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
           pk[e] = pack_bf16x2(p0, p1);
         }
         uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        pf[kb][j] = __builtin_bit_cast(bf16x8, u);
+        pf[2 * kb + j] = __builtin_bit_cast(bf16x8, u);
       }
     if (!C::ONES) l_run = l_run * alpha + psum;
     if (__any(alpha != 1.0f)) {
@@ -218,23 +244,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[mt][v] *= alpha;
     }
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T  (independent accumulators alternate on the MFMA pipe)
+    load_vf(2);
+    load_vf(3);
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) {
-      const int row = mt * 32 + lr;
-      const uint8_t* vrow = sv + row * (BKV * 2);
-      const int sw = row & 15;
+    for (int G = 0; G < 4; ++G)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int ua = 8 * kb + 4 * j + lg;
-          const uint2 lo = *reinterpret_cast<const uint2*>(vrow + ((ua ^ sw) << 3));
-          const uint2 hi = *reinterpret_cast<const uint2*>(vrow + (((ua + 2) ^ sw) << 3));
-          const uint4 u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), pf[kb][j], o[mt], 0, 0, 0);
-        }
-    }
+      for (int mt = 0; mt < C::MT; ++mt)
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt][G], pf[G], o[mt], 0, 0, 0);
+
     if (t + 1 < n_tiles) store_tile((t + 1) & 1);
     __syncthreads();
   }

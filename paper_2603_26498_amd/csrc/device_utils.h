@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace tcmv {
 
@@ -27,6 +28,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // GELU, erf form: x/2 * (1 + erf(x / sqrt 2))
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for_impl(F& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for_impl<I + 1, N>(f);
+  }
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl<0, N>(f); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
