@@ -60,13 +60,32 @@ def softmax_rows(s):
     return p / p.sum(axis=-1, keepdims=True)
 
 
+def attend(q_rows, kk, vv, scale, return_probs=False):
+    """softmax(q k^T * scale) v for some query rows against ALL keys kk / values vv
+    of their segment (one head)."""
+    p = softmax_rows((q_rows @ kk.T) * scale)
+    return (p @ vv, p) if return_probs else p @ vv
+
+
 def attention(q, k, v, cu_seqlens: Sequence[int], heads: int, q_block: int = 1024,
-              return_probs: bool = False):
+              return_probs: bool = False, rows=None):
     """q, k, v: [T, d].  Block-diagonal bidirectional attention: rows
-    cu_seqlens[i]:cu_seqlens[i+1] form segment i."""
+    cu_seqlens[i]:cu_seqlens[i+1] form segment i.  With `rows` (sorted global
+    row indices) only those query rows are evaluated and returned, in order."""
     T, d = q.shape
     dh = d // heads
     scale = 1.0 / np.sqrt(dh)
+    if rows is not None:
+        rows = np.asarray(rows, np.int64)
+        out = np.zeros((len(rows), d), q.dtype)
+        seg = np.searchsorted(np.asarray(cu_seqlens), rows, side="right") - 1
+        for s in np.unique(seg):
+            a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+            sel = np.nonzero(seg == s)[0]
+            for h in range(heads):
+                c = slice(h * dh, (h + 1) * dh)
+                out[sel, c] = attend(q[rows[sel], c], k[a:b, c], v[a:b, c], scale)
+        return out
     out = np.zeros_like(q)
     probs = []
     for s in range(len(cu_seqlens) - 1):
@@ -78,10 +97,11 @@ def attention(q, k, v, cu_seqlens: Sequence[int], heads: int, q_block: int = 102
             kk, vv = k[a:b, c], v[a:b, c]
             for r in range(a, b, q_block):
                 r1 = min(b, r + q_block)
-                p = softmax_rows((q[r:r1, c] @ kk.T) * scale)
-                out[r:r1, c] = p @ vv
                 if return_probs:
+                    out[r:r1, c], p = attend(q[r:r1, c], kk, vv, scale, True)
                     probs.append(p)
+                else:
+                    out[r:r1, c] = attend(q[r:r1, c], kk, vv, scale)
     return (out, probs) if return_probs else out
 
 
@@ -139,12 +159,16 @@ def embed(patches_per_item: List[np.ndarray], grids, desc, weights, dtype=np.flo
     return x + position_rows(desc, grids, weights, dtype)
 
 
-def encoder_block(x, cu, desc, weights, l, dtype=np.float64):
+def encoder_block(x, cu, desc, weights, l, dtype=np.float64, rows=None):
+    """One pre-LN block.  With `rows`, only those output rows are computed (the
+    keys and values of every row are still needed and are computed)."""
     g = lambda n: weights[f"l{l}.{n}"].astype(dtype)
     d = desc.d
     h = layernorm(x, g("ln1_g"), g("ln1_b"), desc.ln_eps)
     qkv = h @ g("w_qkv").T + g("b_qkv")
-    o = attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], cu, desc.heads)
+    o = attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], cu, desc.heads, rows=rows)
+    if rows is not None:
+        x = x[np.asarray(rows, np.int64)]
     x = x + (o @ g("w_o").T + g("b_o"))
     h = layernorm(x, g("ln2_g"), g("ln2_b"), desc.ln_eps)
     h = gelu(h @ g("w_1").T + g("b_1"))

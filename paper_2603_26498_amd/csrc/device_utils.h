@@ -29,6 +29,23 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // GELU, erf form: x/2 * (1 + erf(x / sqrt 2))
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
+// GELU for bf16 outputs: erf from the Abramowitz-Stegun rational approximation
+// 7.1.26 (|error| <= 1.5e-7), far below the bf16 rounding of the result, at about
+// a third of the instructions of the library erff.
+__device__ __forceinline__ float gelu_fast(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
+  const float erf_abs = fmaf(-p, e, 1.0f);          // erf(|x|/sqrt2)
+  const float half_x = 0.5f * x;
+  return fmaf(fabsf(half_x), erf_abs, half_x);      // x/2 * (1 + sign(x) erf_abs)
+}
+
 // compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>)
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for_impl(F& f) {

@@ -6,15 +6,22 @@
 // that the per-lane 16-byte MFMA operand reads (32 rows x same chunk) spread over
 // all banks.  LDS is double buffered and the next tile's global loads are issued
 // before the current tile's MFMAs.  Each wave owns a (BM/WM) x (BN/WN) sub-tile
-// built from v_mfma_f32_32x32x16_bf16; in the accumulator layout a lane holds
-// one output column and 16 rows, so bias is one value per lane and row-major
-// stores of a 32-wide tile are 64/128-byte segments.
+// built from v_mfma_f32_32x32x16_bf16.
+//
+// The MFMA is issued with W as the row operand and A as the column operand, so
+// the accumulator holds C^T: a lane owns ONE output row (token) and, per 32x32
+// tile, four groups of four consecutive output columns.  The epilogue therefore
+// works on 4-wide vectors: one 16-byte read-modify-write for the fp32 residual,
+// one 8-byte store for bf16 outputs, a float4 of bias / position values; and the
+// transposed-V store of the QKV projection has consecutive lanes on consecutive
+// tokens (64-byte segments).
 //
 // Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each walk
 // a contiguous range of tiles: neighbouring tiles share A rows or W rows in the
 // XCD's own L2.
 #include "tcmv_internal.h"
 #include "device_utils.h"
+#include <cstdlib>
 
 namespace tcmv {
 
@@ -110,47 +117,65 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
     if (kt + 1 < nk) store_tiles((kt + 1) & 1);
     __syncthreads();
   }
 
-  // ---- epilogue: lane holds column (lane & 31) and rows 8*(v/4) + 4*(lane>>5) + v%4 of each 32x32 tile
+  // ---- epilogue: lane holds row (lane & 31) and columns 8*(v/4) + 4*(lane>>5) + v%4 of each 32x32 tile
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    const int col = n0 + wn * TN + ni * 32 + lr;
-    if (col >= g.n) continue;
-    const float bias = g.bias ? g.bias[col] : 0.f;
+  for (int mi = 0; mi < MI; ++mi) {
+    const int64_t row = m0 + wm * TM + mi * 32 + lr;
+    if (row >= g.m) continue;
+    int64_t dst = row;
+    int pi = 0, vc = 0;
+    if (EPI == EPI_EMBED) {
+      if (g.dst_row) dst = g.dst_row[row];
+      if (g.pos_idx) pi = g.pos_idx[row];
+    }
+    if (EPI == EPI_QKV) vc = g.vcol[row];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
+    for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t row = m0 + wm * TM + mi * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-        if (row >= g.m) continue;
-        float val = acc[mi][ni][v] + bias;
-        if (EPI == EPI_STORE) {
-          reinterpret_cast<uint16_t*>(g.c)[(size_t)row * g.ldc + col] = f32_to_bf16(val);
-        } else if (EPI == EPI_GELU) {
-          reinterpret_cast<uint16_t*>(g.c)[(size_t)row * g.ldc + col] = f32_to_bf16(gelu_erf(val));
+      for (int vq = 0; vq < 4; ++vq) {
+        const int col = n0 + wn * TN + ni * 32 + 8 * vq + 4 * lg;
+        if (col >= g.n) continue;
+        float4 val = make_float4(acc[mi][ni][4 * vq], acc[mi][ni][4 * vq + 1], acc[mi][ni][4 * vq + 2],
+                                 acc[mi][ni][4 * vq + 3]);
+        if (g.bias) {
+          const float4 b4 = *reinterpret_cast<const float4*>(g.bias + col);
+          val.x += b4.x; val.y += b4.y; val.z += b4.z; val.w += b4.w;
+        }
+        if (EPI == EPI_STORE || EPI == EPI_GELU || (EPI == EPI_QKV && col < g.split)) {
+          if (EPI == EPI_GELU) {
+            val.x = gelu_fast(val.x); val.y = gelu_fast(val.y); val.z = gelu_fast(val.z); val.w = gelu_fast(val.w);
+          }
+          uint2 pk;
+          pk.x = pack_bf16x2(val.x, val.y);
+          pk.y = pack_bf16x2(val.z, val.w);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
         } else if (EPI == EPI_RESID) {
-          float* c = reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col;
-          *c = *c + val;
+          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
+          float4 old = *c;
+          old.x += val.x; old.y += val.y; old.z += val.z; old.w += val.w;
+          *c = old;
         } else if (EPI == EPI_EMBED) {
-          const int pi = g.pos_idx ? g.pos_idx[row] : 0;
           if (g.pos_kind == 1) {
-            val += g.pos0[(size_t)pi * g.n + col];
+            const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)pi * g.n + col);
+            val.x += p0.x; val.y += p0.y; val.z += p0.z; val.w += p0.w;
           } else if (g.pos_kind == 2) {
-            val += g.pos0[(size_t)(pi & 0xFFFF) * g.n + col] + g.pos1[(size_t)(pi >> 16) * g.n + col];
+            const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)(pi & 0xFFFF) * g.n + col);
+            const float4 p1 = *reinterpret_cast<const float4*>(g.pos1 + (size_t)(pi >> 16) * g.n + col);
+            val.x += p0.x + p1.x; val.y += p0.y + p1.y; val.z += p0.z + p1.z; val.w += p0.w + p1.w;
           }
-          const int64_t dst = g.dst_row ? (int64_t)g.dst_row[row] : row;
-          reinterpret_cast<float*>(g.c)[(size_t)dst * g.ldc + col] = val;
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col) = val;
         } else if (EPI == EPI_QKV) {
-          if (col < g.split) {
-            reinterpret_cast<uint16_t*>(g.c)[(size_t)row * g.ldc + col] = f32_to_bf16(val);
-          } else {
-            reinterpret_cast<uint16_t*>(g.vt)[(size_t)(col - g.split) * g.ldvt + g.vcol[row]] = f32_to_bf16(val);
-          }
+          uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
+          vt[0] = f32_to_bf16(val.x);
+          vt[g.ldvt] = f32_to_bf16(val.y);
+          vt[2 * g.ldvt] = f32_to_bf16(val.z);
+          vt[3 * g.ldvt] = f32_to_bf16(val.w);
         }
       }
     }
@@ -189,7 +214,15 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   if (a.m == 0 || a.n == 0) return hipSuccess;
-  if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0) return hipErrorInvalidValue;
+  if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return hipErrorInvalidValue;
+  if (a.epi == EPI_QKV && (a.split % 4)) return hipErrorInvalidValue;
+  static const int big = []{ const char* e = getenv("TCMV_GEMM_BIG"); return e ? atoi(e) : 0; }();
+  if (big == 1) return launch_cfg<256, 256, 2, 2>(a, s);
+  if (big == 2) return launch_cfg<256, 128, 2, 2>(a, s);
+  if (big == 3) return launch_cfg<256, 256, 2, 4>(a, s);
+  if (big == 4) return launch_cfg<256, 256, 4, 2>(a, s);
+  if (big == 5) return launch_cfg<128, 256, 2, 2>(a, s);
+  if (big == 6) return launch_cfg<256, 128, 4, 2>(a, s);
   return launch_cfg<128, 128, 2, 2>(a, s);
 }
 

@@ -238,3 +238,16 @@ def test_attention_energy_note():
     wl = workloads.small_config(4, random_affine=False)
     r = oracle.run(wl)
     assert np.isfinite(r["out"]).all()
+
+
+def test_row_subset_evaluation_equals_full_evaluation():
+    """The row-subset mode used for full-size checks returns exactly the rows of the full result."""
+    desc = _tiny(pos="none", layers=1)
+    w = workloads.make_weights(desc, 21, random_affine=True, std=0.3)
+    rng = np.random.default_rng(21)
+    x = rng.normal(size=(40, desc.d))
+    cu = np.array([0, 7, 7, 25, 40])
+    rows = [0, 6, 7, 24, 25, 39]
+    full = oe.encoder_block(x, cu, desc, w, 0)
+    part = oe.encoder_block(x, cu, desc, w, 0, rows=rows)
+    assert np.abs(full[rows] - part).max() <= 1e-13
