@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -55,6 +56,14 @@ int fail(tcmv_ctx* ctx, int code, const std::string& msg) {
 }
 int fail_hip(tcmv_ctx* ctx, hipError_t e, const char* what) {
   return fail(ctx, TCMV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// query rows per attention work item on the bf16 path: two query tiles per wave
+// where the register file allows it (head size up to 80), one otherwise
+int attn_bq_bf16(int dh) {
+  static const int forced = [] { const char* e = getenv("TCMV_ATTN_BQ"); return e ? atoi(e) : 0; }();
+  if (forced == 128 || forced == 256) return forced;
+  return dh <= 80 ? 256 : 128;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -373,7 +382,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     seg_start.push_back(row0);
     seg_len.push_back(rows);
     seg_v0.push_back(p->t_vpad);
-    for (int64_t r = 0; r < rows; ++r) p->row_vcol.push_back((int32_t)(p->t_vpad + r));
+    for (int64_t r = 0; r < rows; ++r) p->row_vcol.push_back((int32_t)(p->t_vpad + vt_col_in_segment(r)));
     p->t_vpad += (rows + kVtAlign - 1) / kVtAlign * kVtAlign;
     p->items.push_back(di);
     p->cu.push_back(row0 + rows);
@@ -381,7 +390,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->n_patch_rows = (int64_t)p->prow_item.size();
   p->n_tokens = p->cu.back();
   p->n_segments = (int)seg_start.size();
-  build_work(p->work, seg_start, seg_len, seg_v0, d.dtype == TCMV_BF16 ? kAttnBQ_bf16 : kAttnBQ_f32);
+  build_work(p->work, seg_start, seg_len, seg_v0, d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads) : kAttnBQ_f32);
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
   for (int c = 0; c < 3; ++c)
@@ -497,6 +506,9 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   hipError_t e;
 #define TCMV_CHECK(call, what) do { e = (call); if (e != hipSuccess) return fail_hip(ctx, e, what); } while (0)
 
+  // the padding columns of the transposed-V buffer must read as zeros in every layer
+  if (bf)
+    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)d.d * p->t_vpad * 2, s); }), "V^T clear");
   // patch embedding (+ position), CLS rows
   {
     GemmArgs g{};
@@ -529,6 +541,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       AttnArgs a{};
       a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size();
       a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = d.d;
+      a.bq = bf ? attn_bq_bf16(dh) : kAttnBQ_f32;
       if (bf) {
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
         a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->t_vpad;
@@ -650,11 +663,11 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   L.T = n_seg > 0 ? cu[n_seg] : 0;
   L.t_vpad = vp;
   std::vector<AttnWork> wtmp;
-  build_work(wtmp, ss, sl, sv, dtype == TCMV_BF16 ? kAttnBQ_bf16 : kAttnBQ_f32);
+  build_work(wtmp, ss, sl, sv, dtype == TCMV_BF16 ? attn_bq_bf16(d / heads) : kAttnBQ_f32);
   if (vcol) {
     vcol->assign((size_t)L.T, 0);
     for (size_t s = 0; s < ss.size(); ++s)
-      for (int64_t r = 0; r < sl[s]; ++r) (*vcol)[(size_t)(ss[s] + r)] = (int32_t)(sv[s] + r);
+      for (int64_t r = 0; r < sl[s]; ++r) (*vcol)[(size_t)(ss[s] + r)] = (int32_t)(sv[s] + vt_col_in_segment(r));
   }
   size_t off = 0;
   L.vcol = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
@@ -700,9 +713,12 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
   AttnArgs a{};
   a.work = reinterpret_cast<const AttnWork*>(wsb + L.work); a.n_work = (int)work.size();
   a.heads = heads; a.dh = dh; a.t_total = L.T; a.out = d_out; a.ldo = d;
+  a.bq = dtype == TCMV_BF16 ? attn_bq_bf16(dh) : kAttnBQ_f32;
   hipError_t e;
   if (dtype == TCMV_BF16) {
     const uint16_t* q = reinterpret_cast<const uint16_t*>(d_qkv);
+    e = launch_fill_zero(wsb + L.vt, (size_t)d * L.t_vpad * 2, s);
+    if (e != hipSuccess) return TCMV_E_HIP;
     e = launch_transpose_v(q + 2 * d, 3 * d, reinterpret_cast<const int32_t*>(wsb + L.vcol), wsb + L.vt, L.t_vpad, L.T, d, s);
     if (e != hipSuccess) return TCMV_E_HIP;
     a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = wsb + L.vt; a.ldv = L.t_vpad;

@@ -1,22 +1,28 @@
 // Bidirectional block-diagonal attention on bf16 MFMA (gfx950), flash style:
 // scores are never written to memory; softmax statistics are kept per query in
-// fp32 and updated tile by tile (online softmax).
+// fp32 and updated block by block (online softmax).
 //
-// Work decomposition: one workgroup (4 waves) = 128 query rows of one segment
-// and one head; each wave owns 32 query rows.  K and V^T tiles of 64 keys are
-// staged in LDS (double buffered, next tile's global loads in flight during the
-// MFMAs) and shared by the four waves.
+// Work decomposition: one workgroup (4 waves) = 32*NT*4 query rows of one
+// segment and one head; each wave owns NT tiles of 32 query rows.  K and V^T
+// tiles of 64 keys are staged in LDS by direct global->LDS loads (double
+// buffered, the next tile's loads are in flight during the MFMAs) and shared by
+// the four waves.  Every K / V^T
+// fragment read from LDS feeds NT MFMAs: LDS bandwidth (about 128 B/clk/CU) is
+// the first limit of this kernel, and NT = 2 halves the LDS bytes per FLOP.
 //
 // The kernel computes S^T = K * Q^T (keys are the MFMA row dimension).  In the
 // 32x32 accumulator layout a lane then holds ONE query column and 16 keys, so
-//   * the running max / rescale factor are one scalar per lane,
+//   * the running max / rescale factor are one scalar per lane and query tile,
 //   * the exponentiated scores, packed to bf16 in place, already have the
 //     register layout of the B operand of O^T += V^T * P^T (the contraction
 //     index only has to be enumerated in the same order on both operands, so V^T
-//     is read from LDS in the key order the accumulator happens to have),
+//     is stored in LDS in the key order the accumulator happens to have),
 //   * P never goes through LDS.
-// V arrives already transposed ([head_dim, keys], keys contiguous) so the V^T
-// operand is two 8-byte LDS reads per MFMA.
+// V arrives already transposed ([head_dim, keys], keys contiguous, the four
+// quarters of every aligned group of 16 keys stored in the order 0,2,1,3 - see
+// the V^T tile comment below) and zero in the padding columns.  The online
+// softmax advances in blocks of 32 keys (one accumulator tile per query tile),
+// which keeps the live score registers at 16*NT.
 //
 // When head_dim is an odd multiple of 16 the V^T tile is padded to a multiple of
 // 32 rows; the first padding row is filled with ones, which makes the MFMA
@@ -24,13 +30,15 @@
 // free; otherwise the denominator is accumulated on the vector ALU.
 #include "tcmv_internal.h"
 #include "device_utils.h"
+#include <algorithm>
 
 namespace tcmv {
 
 namespace {
-constexpr int BQ = kAttnBQ_bf16;
 constexpr int BKV = 64;
 constexpr int NTHREADS = 256;
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 }  // namespace
 
 template <int DH>
@@ -44,19 +52,23 @@ struct AttnCfg {
   static constexpr int K_BYTES = BKV * KSTR;
   static constexpr int V_BYTES = DHP * BKV * 2;
   static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int NCH_K = BKV * KCH, NCH_V = DH * (BKV / 8);
-  static constexpr int NLOAD = (NCH_K + NCH_V) / NTHREADS;   // 16-byte global loads per thread per tile
-  static_assert((NCH_K + NCH_V) % NTHREADS == 0, "tile does not split evenly over the workgroup");
+  static constexpr int KROWCH = KCH | 1;                   // chunks per K row in LDS incl. padding
+  static constexpr int NW = KROWCH + DH / 8;               // wave-wide 1 KB loads per tile (K rows, then V^T rows)
+  static constexpr int NI = (NW + 3) / 4;                  // loads per wave (4 waves)
 };
 
 // V^T tile in LDS: row = head-dim index (128 bytes = 64 keys).  Inside a row the
 // keys are stored in the order the PV MFMA wants them: 16-byte chunk (2G + g)
 // holds keys {16G + 4g + 0..3, 16G + 8 + 4g + 0..3}, i.e. exactly the 8 keys a
-// lane of half-wave g contributes to k-step G.  Chunks are XOR-swizzled by the
-// row so that 32 lanes reading the same chunk of 32 different rows hit all banks.
-template <int DH>
+// lane of half-wave g contributes to k-step G.  The transposed-V buffer in
+// global memory already has this key order (the producer writes key kk of a
+// 16-group at position [0,2,1,3][kk/4]*4 + kk%4), so a chunk is one 16-byte
+// global load.  Chunks are XOR-swizzled by the row so that 32 lanes reading the
+// same chunk of 32 different rows hit all banks.
+template <int DH, int NT>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
+  constexpr int WQ = 32 * NT;             // query rows per wave
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::STAGE];
 
   const int total = a.n_work * a.heads;
@@ -85,202 +97,207 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 
   // query fragments (B operand of S^T = K Q^T), kept in registers for the whole kernel
-  bf16x8 qf[C::KS];
-  {
-    int qi = wave * 32 + lr;
+  bf16x8 qf[NT][C::KS];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int qi = wave * WQ + nt * 32 + lr;
     if (qi >= w.nq) qi = w.nq - 1;
     const uint16_t* qp = Q + (size_t)(w.q0 + qi) * a.ldqk + head * DH + lg * 8;
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    for (int ks = 0; ks < C::KS; ++ks) qf[nt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
-  // global -> register staging of one K / V^T tile: NLOAD 16-byte chunks per thread;
-  // chunk ids [0, NCH_K) are K, the rest V^T.  Source pointers and LDS offsets are
-  // selected arithmetically (no divergent control flow) and computed once.
-  uint4 rg[C::NLOAD];
-  const uint16_t* gsrc[C::NLOAD];   // source of tile 0; K advances by 64 rows, V^T by 64 columns per tile
-  int lds_lo[C::NLOAD], lds_hi[C::NLOAD];   // byte offsets of the two 8-byte halves inside a stage
-  int vkey0[C::NLOAD];              // V^T chunks: first key of the chunk inside the tile, K chunks: -1
-  int krow[C::NLOAD];               // K chunks: row inside the tile
+  // Tile staging: global -> LDS directly (no registers, no LDS store instructions).  One
+  // wave-wide load writes 64 consecutive 16-byte chunks of LDS (base + lane*16), so each
+  // lane fetches the global chunk that belongs at its LDS position: K rows are stored
+  // with a padding chunk (odd chunk count per row), V^T chunks at their swizzled position.
+  // The tile is C::NW wave-loads; wave w issues loads w, w+4, w+8, ...
+  uint32_t goff[C::NI];             // element offset of this lane's tile-0 chunk from K (or VT)
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
-  for (int i = 0; i < C::NLOAD; ++i) {
-    const int c = tid + i * NTHREADS;
-    const bool is_k = c < C::NCH_K;
-    const int rowk = c / C::KCH, cck = c - rowk * C::KCH;
-    const int cv = c - C::NCH_K;
-    const int rowv = cv >> 3, ccv = cv & 7;
-    const int G = ccv >> 1, h = ccv & 1, sw = rowv & 7;
-    const int vb = C::K_BYTES + rowv * (BKV * 2) + h * 8;
-    lds_lo[i] = is_k ? rowk * C::KSTR + cck * 16 : vb + (((2 * G) ^ sw) << 4);
-    lds_hi[i] = is_k ? rowk * C::KSTR + cck * 16 + 8 : vb + (((2 * G + 1) ^ sw) << 4);
-    vkey0[i] = is_k ? -1 : ccv * 8;
-    krow[i] = is_k ? rowk : 0;
-    const uint16_t* ks = K + (size_t)head * DH + (size_t)(w.seg_start + rowk) * a.ldqk + cck * 8;
-    const uint16_t* vs = VT + ((size_t)head * DH + rowv) * a.ldv + w.v0 + ccv * 8;
-    gsrc[i] = is_k ? ks : vs;
+  for (int i = 0; i < C::NI; ++i) {
+    const int n = wave_u + 4 * i;
+    const int L = n * 64 + lane;                       // K part: chunk index incl. padding chunks
+    const int rowk = L / C::KROWCH;
+    int cck = L - rowk * C::KROWCH;
+    if (cck >= C::KCH) cck = 0;                        // padding chunk: any valid source
+    const int Lv = (n - C::KROWCH) * 64 + lane;        // V^T part
+    const int rowv = Lv >> 3, lc = (Lv & 7) ^ (rowv & 7);
+    const uint32_t ko = (uint32_t)(head * DH) + (uint32_t)(w.seg_start + rowk) * (uint32_t)a.ldqk + cck * 8;
+    const uint32_t vo = (uint32_t)(head * DH + rowv) * (uint32_t)a.ldv + (uint32_t)w.v0 + lc * 8;
+    goff[i] = (n < C::KROWCH) ? ko : vo;
   }
-  const int64_t kstep = (int64_t)BKV * a.ldqk;
-  auto load_tile = [&](int t, bool tail) {
+  const uint32_t kstep = (uint32_t)BKV * (uint32_t)a.ldqk;
+  auto load_tile = [&](int t, int buf, bool tail) {
 #pragma unroll
-    for (int i = 0; i < C::NLOAD; ++i) {
-      const bool is_k = vkey0[i] < 0;
-      const uint16_t* src = gsrc[i] + (is_k ? (int64_t)t * kstep : (int64_t)t * BKV);
-      if (tail && is_k) {   // last tile: rows past the end of the buffer are clamped (their scores are masked)
-        const int64_t over = (int64_t)w.seg_start + t * BKV + krow[i] - (a.t_total - 1);
-        if (over > 0) src -= over * a.ldqk;
+    for (int i = 0; i < C::NI; ++i) {
+      const int n = wave_u + 4 * i;
+      if (n < C::NW) {
+        const bool is_k = n < C::KROWCH;
+        uint32_t off = goff[i] + (is_k ? (uint32_t)t * kstep : (uint32_t)t * BKV);
+        if (tail && is_k) {   // last tile: rows past the end of the buffer are clamped (their scores are masked)
+          const int rowk = (n * 64 + lane) / C::KROWCH;
+          const int64_t over = (int64_t)w.seg_start + t * BKV + rowk - (a.t_total - 1);
+          if (over > 0) off -= (uint32_t)over * (uint32_t)a.ldqk;
+        }
+        const uint16_t* src = (is_k ? K : VT) + off;
+        uint8_t* dst = smem + buf * C::STAGE + (is_k ? n * 1024 : C::K_BYTES + (n - C::KROWCH) * 1024);
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
       }
-      uint4 v = *reinterpret_cast<const uint4*>(src);
-      if (tail && !is_k) {  // keys beyond the segment: force exact zeros (the buffer may hold anything there)
-        const int valid = w.seg_len - (t * BKV + vkey0[i]);
-        v.x = (valid <= 0) ? 0u : (valid == 1 ? (v.x & 0xFFFFu) : v.x);
-        v.y = (valid <= 2) ? 0u : (valid == 3 ? (v.y & 0xFFFFu) : v.y);
-        v.z = (valid <= 4) ? 0u : (valid == 5 ? (v.z & 0xFFFFu) : v.z);
-        v.w = (valid <= 6) ? 0u : (valid == 7 ? (v.w & 0xFFFFu) : v.w);
-      }
-      rg[i] = v;
     }
   };
-  auto store_tile = [&](int buf) {
-    uint8_t* st = smem + buf * C::STAGE;
-#pragma unroll
-    for (int i = 0; i < C::NLOAD; ++i) {
-      *reinterpret_cast<uint2*>(st + lds_lo[i]) = make_uint2(rg[i].x, rg[i].y);
-      *reinterpret_cast<uint2*>(st + lds_hi[i]) = make_uint2(rg[i].z, rg[i].w);
-    }
-  };
+  auto wait_tile = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
-  f32x16 o[C::MT];
+  f32x16 o[C::MT][NT];
 #pragma unroll
   for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[mt][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mt][nt][v] = 0.f;
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
   const float cs = a.scale;   // softmax scale * log2(e)
 
   const int n_tiles = (w.seg_len + BKV - 1) / BKV;
   const bool ragged = (w.seg_len % BKV) != 0;
-  load_tile(0, ragged && n_tiles == 1);
-  store_tile(0);
+  load_tile(0, 0, ragged && n_tiles == 1);
+  wait_tile();
   __syncthreads();
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int j0 = t * BKV;
-    if (t + 1 < n_tiles) load_tile(t + 1, ragged && (t + 2 == n_tiles));
-    const uint8_t* sk = smem + (t & 1) * C::STAGE;
-    const uint8_t* sv = sk + C::K_BYTES;
-
-    // ---- S^T tile: 64 keys x 32 queries.  All K fragments are requested first so
-    // that the LDS latency overlaps; the two key blocks alternate on the MFMA pipe.
-    bf16x8 kf[2][C::KS];
+  // S^T block: 32 keys (block kb of the staged tile) x 32*NT queries
+  auto score_block = [&](const uint8_t* sk, int kb, f32x16 (&s)[NT]) {
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks)
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        kf[kb][ks] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
-    f32x16 s[2];
+      for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int ks = 0; ks < C::KS; ++ks) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+      for (int nt = 0; nt < NT; ++nt)
+        s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][ks], s[nt], 0, 0, 0);
+    }
+  };
+  // online softmax of one block (per lane = per query column); returns packed probabilities.
+  // The running reference m_run only moves when the block maximum exceeds it by more than
+  // kLazy (in log2 units): probabilities may then exceed 1 (by at most 2^kLazy), which
+  // changes nothing mathematically because numerator and denominator share the reference,
+  // and it makes the rescaling of O rare.
+  constexpr float kLazy = 8.0f;
+  auto softmax_block = [&](f32x16 (&s)[NT], bf16x8 (&pf)[NT][2], int key0, bool mask) {
+    if (mask) {
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[ks], s[kb], 0, 0, 0);
-
-    // V^T fragments of the first two k-steps are requested before the softmax arithmetic
-    bf16x8 vf[C::MT][4];
-    auto load_vf = [&](int G) {
-#pragma unroll
-      for (int mt = 0; mt < C::MT; ++mt) {
-        const int row = mt * 32 + lr;
-        vf[mt][G] = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * G + lg) ^ (row & 7)) << 4));
-      }
-    };
-    load_vf(0);
-    load_vf(1);
-
-    if (ragged && t + 1 == n_tiles) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int key = j0 + kb * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-          if (key >= w.seg_len) s[kb][v] = -INFINITY;
+          const int key = key0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+          if (key >= w.seg_len) s[nt][v] = -INFINITY;
         }
     }
-    // ---- online softmax (per lane = per query column)
-    float mx = s[0][0];
+    bool need_rescale = false;
+    float alpha[NT];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int nt = 0; nt < NT; ++nt) {
+      float mx = s[nt][0];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cs);
-    m_run = m_new;
-    const float mc = m_new * cs;
-    bf16x8 pf[4];     // pf[G]: keys of k-step G = 2*kb + j
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[nt][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const bool move = (mx - m_run[nt]) * cs > kLazy;     // also true for the first block (m_run = -inf)
+      const float m_new = move ? mx : m_run[nt];
+      alpha[nt] = move ? __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs) : 1.0f;
+      m_run[nt] = m_new;
+      need_rescale = need_rescale || move;
+      const float mc = m_new * cs;
+      float psum = 0.f;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         uint32_t pk[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * j + 2 * e], cs, -mc));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * j + 2 * e + 1], cs, -mc));
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[nt][8 * j + 2 * e], cs, -mc));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[nt][8 * j + 2 * e + 1], cs, -mc));
           if (!C::ONES) psum += p0 + p1;
           pk[e] = pack_bf16x2(p0, p1);
         }
         uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        pf[2 * kb + j] = __builtin_bit_cast(bf16x8, u);
+        pf[nt][j] = __builtin_bit_cast(bf16x8, u);
       }
-    if (!C::ONES) l_run = l_run * alpha + psum;
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-      for (int mt = 0; mt < C::MT; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[mt][v] *= alpha;
+      if (!C::ONES) l_run[nt] = l_run[nt] * alpha[nt] + psum;
     }
-    // ---- O^T += V^T P^T  (independent accumulators alternate on the MFMA pipe)
-    load_vf(2);
-    load_vf(3);
-#pragma unroll
-    for (int G = 0; G < 4; ++G)
+    if (__any(need_rescale)) {
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt)
-        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt][G], pf[G], o[mt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[mt][nt][v] *= alpha[nt];
+    }
+  };
+  // O^T += V^T P^T for the 32 keys of block kb (two k-steps of 16 keys)
+  auto pv_block = [&](const uint8_t* sv, int kb, const bf16x8 (&pf)[NT][2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        const int row = mt * 32 + lr;
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ (row & 7)) << 4));
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][j], o[mt][nt], 0, 0, 0);
+      }
+  };
 
-    if (t + 1 < n_tiles) store_tile((t + 1) & 1);
+  // Software pipeline over 32-key blocks: the score MFMAs of the next block are issued
+  // before the softmax arithmetic of the current one, so the matrix pipe and the vector
+  // ALU of one wave overlap:   S(t,1) || softmax(t,0) ;  PV(t,0) || softmax(t,1) ;  PV(t,1).
+  f32x16 s0[NT], s1[NT];
+  score_block(smem, 0, s0);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    if (t + 1 < n_tiles) load_tile(t + 1, (t + 1) & 1, ragged && (t + 2 == n_tiles));
+    const uint8_t* sk = smem + (t & 1) * C::STAGE;
+    const uint8_t* sv = sk + C::K_BYTES;
+    const bool mask_tile = ragged && t + 1 == n_tiles;
+    bf16x8 p0[NT][2], p1[NT][2];
+    score_block(sk, 1, s1);
+    softmax_block(s0, p0, j0, mask_tile);
+    pv_block(sv, 0, p0);
+    softmax_block(s1, p1, j0 + 32, mask_tile);
+    pv_block(sv, 1, p1);
+    wait_tile();
     __syncthreads();
+    if (t + 1 < n_tiles) score_block(smem + ((t + 1) & 1) * C::STAGE, 0, s0);
   }
 
   // ---- normalise and store: lane holds query (lane & 31), head-dim rows 8*(v/4) + 4*lg + v%4
-  float l;
-  if (C::ONES) {
-    constexpr int r = DH % 32;                       // row of the ones line inside its tile (16)
-    l = __shfl(o[DH / 32][4 * (r / 8)], lr, 64);     // held by the lanes of the lower half-wave
-  } else {
-    l = l_run + __shfl_xor(l_run, 32, 64);
-  }
-  const float inv = 1.0f / l;
-  const int qi = wave * 32 + lr;
-  if (qi < w.nq) {
-    uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + (size_t)(w.q0 + qi) * a.ldo + head * DH;
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt)
+  for (int nt = 0; nt < NT; ++nt) {
+    float l;
+    if (C::ONES) {
+      constexpr int r = DH % 32;                          // row of the ones line inside its tile (16)
+      l = __shfl(o[DH / 32][nt][4 * (r / 8)], lr, 64);    // held by the lanes of the lower half-wave
+    } else {
+      l = l_run[nt] + __shfl_xor(l_run[nt], 32, 64);
+    }
+    const float inv = 1.0f / l;
+    const int qi = wave * WQ + nt * 32 + lr;
+    if (qi < w.nq) {
+      uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + (size_t)(w.q0 + qi) * a.ldo + head * DH;
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int dh0 = mt * 32 + 8 * vq + 4 * lg;
-        if (dh0 < DH) {
-          uint2 pk;
-          pk.x = pack_bf16x2(o[mt][4 * vq] * inv, o[mt][4 * vq + 1] * inv);
-          pk.y = pack_bf16x2(o[mt][4 * vq + 2] * inv, o[mt][4 * vq + 3] * inv);
-          *reinterpret_cast<uint2*>(op + dh0) = pk;
+      for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int dh0 = mt * 32 + 8 * vq + 4 * lg;
+          if (dh0 < DH) {
+            uint2 pk;
+            pk.x = pack_bf16x2(o[mt][nt][4 * vq] * inv, o[mt][nt][4 * vq + 1] * inv);
+            pk.y = pack_bf16x2(o[mt][nt][4 * vq + 2] * inv, o[mt][nt][4 * vq + 3] * inv);
+            *reinterpret_cast<uint2*>(op + dh0) = pk;
+          }
         }
-      }
+    }
   }
 }
 
@@ -289,16 +306,32 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.n_work * a.heads;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
+  if (a.bq != 128 && a.bq != 256) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-#define TCMV_ATTN_CASE(D)                                                                      \
-  case D:                                                                                      \
-    hipLaunchKernelGGL((attn_bf16_kernel<D>), dim3(grid), dim3(NTHREADS), 0, s, a);            \
+#define TCMV_ATTN_CASE(D)                                                                         \
+  case D:                                                                                         \
+    if (a.bq == 256) hipLaunchKernelGGL((attn_bf16_kernel<D, 2>), dim3(grid), dim3(NTHREADS), 0, s, a); \
+    else hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), dim3(grid), dim3(NTHREADS), 0, s, a);       \
     break;
   switch (a.dh) {
     TCMV_ATTN_CASE(32) TCMV_ATTN_CASE(64) TCMV_ATTN_CASE(80) TCMV_ATTN_CASE(96)
     default: return hipErrorInvalidValue;
   }
 #undef TCMV_ATTN_CASE
+  return hipGetLastError();
+}
+
+// zero fill (16-byte stores); n16 = number of 16-byte units
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16 || reinterpret_cast<uintptr_t>(p) % 16) return hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
   return hipGetLastError();
 }
 

@@ -53,6 +53,7 @@ struct AttnArgs {
   void* out; int64_t ldo;
   const AttnWork* work; int n_work;
   int heads, dh;
+  int bq;                                        // query rows per work item the list was built with (bf16: 128 or 256)
   int64_t t_total;                               // rows of q/k (for clamping)
   float scale;
 };
@@ -78,13 +79,24 @@ hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
 // vt[c][vcol[r]] = v[r][c] for r < rows, c < d  (bf16)
 hipError_t launch_transpose_v(const void* v, int64_t ldv, const int32_t* vcol, void* vt, int64_t ldvt,
                               int64_t rows, int d, hipStream_t s);
+// zero fill of a 16-byte aligned region whose size is a multiple of 16
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 // hidden[cls_rows[i]] = cls + pos0[0] (if pos0)
 hipError_t launch_cls_rows(float* hidden, const int32_t* cls_rows, int n, const float* cls,
                            const float* pos0, int d, hipStream_t s);
 
 // Tile sizes the host must know about.
-constexpr int kAttnBQ_bf16 = 128;   // query rows per attention workgroup, bf16 path
 constexpr int kAttnBQ_f32 = 64;     // query rows per attention workgroup, fp32 path
 constexpr int kVtAlign = 64;        // segment starts in the transposed-V buffer are multiples of this
+
+// Column of key r (row inside its segment) in the transposed-V buffer, relative to the
+// segment's first column: inside every aligned group of 16 keys the four quarters are
+// stored in the order 0, 2, 1, 3 (the order the attention kernel's MFMA operand wants).
+inline int64_t vt_col_in_segment(int64_t r) {
+  const int64_t kk = r & 15;
+  const int64_t q = kk >> 2;
+  const int64_t nq = (q == 1) ? 2 : (q == 2 ? 1 : q);
+  return (r & ~(int64_t)15) + nq * 4 + (kk & 3);
+}
 
 }  // namespace tcmv
