@@ -12,7 +12,7 @@ import numpy as np
 from . import preprocess, encoder, naive  # noqa: F401
 
 
-def run(workload, dtype=np.float64, stages=("preprocess", "encode", "merge"), progress=None):
+def run(workload, dtype=np.float64, stages=("preprocess", "encode", "merge"), progress=None, workers=1):
     """Run the whole path for a workload (see workloads.Workload).
 
     Returns a dict with 'patches' (list per request), 'cu_seqlens', 'hidden'
@@ -24,7 +24,7 @@ def run(workload, dtype=np.float64, stages=("preprocess", "encode", "merge"), pr
     res["cu_seqlens"] = encoder.cu_seqlens_of(grids, desc.use_cls)
     res["patches"] = [preprocess.preprocess_item(it, desc) for it in items]
     if "encode" in stages:
-        res["hidden"] = encoder.encode(res["patches"], grids, desc, w, dtype, progress)
+        res["hidden"] = encoder.encode(res["patches"], grids, desc, w, dtype, progress, workers)
         if "merge" in stages and desc.out_dim:
             res["out"] = encoder.merge_project(res["hidden"], desc, w, dtype)
     return res

@@ -68,11 +68,24 @@ def attend(q_rows, kk, vv, scale, return_probs=False):
 
 
 def attention(q, k, v, cu_seqlens: Sequence[int], heads: int, q_block: int = 1024,
-              return_probs: bool = False, rows=None):
+              return_probs: bool = False, rows=None, workers: int = 1):
     """q, k, v: [T, d].  Block-diagonal bidirectional attention: rows
     cu_seqlens[i]:cu_seqlens[i+1] form segment i.  With `rows` (sorted global
-    row indices) only those query rows are evaluated and returned, in order."""
+    row indices) only those query rows are evaluated and returned, in order.
+    `workers` > 1 evaluates the (independent) heads on a thread pool; the
+    arithmetic of every head is unchanged."""
     T, d = q.shape
+    if workers > 1 and rows is None and not return_probs:
+        from concurrent.futures import ThreadPoolExecutor
+        dh = d // heads
+        out = np.zeros_like(q)
+
+        def one(h):
+            c = slice(h * dh, (h + 1) * dh)
+            out[:, c] = attention(q[:, c], k[:, c], v[:, c], cu_seqlens, 1, q_block)
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(one, range(heads)))
+        return out
     dh = d // heads
     scale = 1.0 / np.sqrt(dh)
     if rows is not None:
@@ -159,14 +172,14 @@ def embed(patches_per_item: List[np.ndarray], grids, desc, weights, dtype=np.flo
     return x + position_rows(desc, grids, weights, dtype)
 
 
-def encoder_block(x, cu, desc, weights, l, dtype=np.float64, rows=None):
+def encoder_block(x, cu, desc, weights, l, dtype=np.float64, rows=None, workers=1):
     """One pre-LN block.  With `rows`, only those output rows are computed (the
     keys and values of every row are still needed and are computed)."""
     g = lambda n: weights[f"l{l}.{n}"].astype(dtype)
     d = desc.d
     h = layernorm(x, g("ln1_g"), g("ln1_b"), desc.ln_eps)
     qkv = h @ g("w_qkv").T + g("b_qkv")
-    o = attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], cu, desc.heads, rows=rows)
+    o = attention(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], cu, desc.heads, rows=rows, workers=workers)
     if rows is not None:
         x = x[np.asarray(rows, np.int64)]
     x = x + (o @ g("w_o").T + g("b_o"))
@@ -176,13 +189,13 @@ def encoder_block(x, cu, desc, weights, l, dtype=np.float64, rows=None):
     return x
 
 
-def encode(patches_per_item, grids, desc, weights, dtype=np.float64, progress=None):
+def encode(patches_per_item, grids, desc, weights, dtype=np.float64, progress=None, workers=1):
     """Patches of every request -> encoder output [T, d] (segments concatenated
     in request order; requests without frames contribute no rows)."""
     cu = cu_seqlens_of(grids, desc.use_cls)
     x = embed(patches_per_item, grids, desc, weights, dtype)
     for l in range(desc.layers):
-        x = encoder_block(x, cu, desc, weights, l, dtype)
+        x = encoder_block(x, cu, desc, weights, l, dtype, workers=workers)
         if progress:
             progress(l)
     if desc.final_ln:

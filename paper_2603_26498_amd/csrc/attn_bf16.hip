@@ -63,8 +63,9 @@ struct AttnCfg {
 // lane of half-wave g contributes to k-step G.  The transposed-V buffer in
 // global memory already has this key order (the producer writes key kk of a
 // 16-group at position [0,2,1,3][kk/4]*4 + kk%4), so a chunk is one 16-byte
-// global load.  Chunks are XOR-swizzled by the row so that 32 lanes reading the
-// same chunk of 32 different rows hit all banks.
+// global load.  Chunks are XOR-swizzled by (row/2)%8: the LDS serves 16 lanes x 16
+// bytes per clock over 64 banks and two 128-byte rows span the banks, so 16
+// consecutive rows reading the same logical chunk land on 16 different bank groups.
 template <int DH, int NT>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     int cck = L - rowk * C::KROWCH;
     if (cck >= C::KCH) cck = 0;                        // padding chunk: any valid source
     const int Lv = (n - C::KROWCH) * 64 + lane;        // V^T part
-    const int rowv = Lv >> 3, lc = (Lv & 7) ^ (rowv & 7);
+    const int rowv = Lv >> 3, lc = (Lv & 7) ^ ((rowv >> 1) & 7);
     const uint32_t ko = (uint32_t)(head * DH) + (uint32_t)(w.seg_start + rowk) * (uint32_t)a.ldqk + cck * 8;
     const uint32_t vo = (uint32_t)(head * DH + rowv) * (uint32_t)a.ldv + (uint32_t)w.v0 + lc * 8;
     goff[i] = (n < C::KROWCH) ? ko : vo;
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt) {
         const int row = mt * 32 + lr;
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ (row & 7)) << 4));
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ ((row >> 1) & 7)) << 4));
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
           o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][j], o[mt][nt], 0, 0, 0);

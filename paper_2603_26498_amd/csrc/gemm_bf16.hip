@@ -1,11 +1,13 @@
 // C = epilogue(A * W^T + bias) on bf16 MFMA (gfx950), fp32 accumulation.
 //
 // A [m, k] and W [n, k] are both contiguous along k, so both operands are staged
-// the same way: 16-byte global loads -> registers -> LDS tile of 64 k-elements
-// per row (128 bytes), with the 16-byte chunk index XOR-swizzled by the row so
-// that the per-lane 16-byte MFMA operand reads (32 rows x same chunk) spread over
-// all banks.  LDS is double buffered and the next tile's global loads are issued
-// before the current tile's MFMAs.  Each wave owns a (BM/WM) x (BN/WN) sub-tile
+// the same way: direct global -> LDS loads (16 bytes per lane, no registers in
+// between) into tiles of 64 k-elements per row (128 bytes), with the 16-byte
+// chunk index XOR-swizzled by (row/2)%8 so that the per-lane 16-byte MFMA operand
+// reads are conflict-free: the LDS serves 16 lanes x 16 bytes per clock over 64
+// banks, two 128-byte rows span the banks, so 16 consecutive rows reading the
+// same logical chunk must land on 16 different 16-byte bank groups.  LDS is double buffered and
+// the next tile's loads are issued before the current tile's MFMAs.  Each wave owns a (BM/WM) x (BN/WN) sub-tile
 // built from v_mfma_f32_32x32x16_bf16.
 //
 // The MFMA is issued with W as the row operand and A as the column operand, so
@@ -25,15 +27,21 @@
 
 namespace tcmv {
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
-  constexpr int NT = WM * WN * 64;
-  constexpr int BK = 64;
+namespace {
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+}  // namespace
+
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, int MINB, int EPI>
+__global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+  constexpr int ROWB = BK * 2;                     // bytes per staged row
+  constexpr int CPR = BK / 8;                      // 16-byte chunks per row (8 or 4)
+  constexpr int SW_SHIFT = (CPR == 8) ? 1 : 2;     // rows that share a swizzle value (span 256 bytes = all banks)
+  constexpr int RPL = 64 / CPR;                    // rows covered by one wave-wide load
+  static_assert(BK == 64 || BK == 32, "BK");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
 
   const int tiles_n = (g.n + BN - 1) / BN;
   const int tiles_m = (int)((g.m + BM - 1) / BM);
@@ -41,7 +49,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
   const int chunk = (total + 7) >> 3;
   const int p = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
   if (p >= total) return;
-  const int tm = p / tiles_n, tn = p - tm * tiles_n;
+  // tiles are walked in groups of GM rows of tiles, column by column inside a group: the
+  // workgroups that run at the same time on one XCD then form a roughly square block of
+  // tiles and share both A rows and W rows in that XCD's L2
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int grp = p / per_group, within = p - grp * per_group;
+  const int gm_eff = min(GM, tiles_m - grp * GM);
+  const int tn = within / gm_eff;
+  const int tm = grp * GM + (within - tn * gm_eff);
   const int64_t m0 = (int64_t)tm * BM;
   const int n0 = tn * BN;
 
@@ -50,36 +66,43 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
   const uint16_t* A = reinterpret_cast<const uint16_t*>(g.a);
   const uint16_t* W = reinterpret_cast<const uint16_t*>(g.w);
 
-  uint4 ra[A_CH], rb[B_CH];
-  auto load_tiles = [&](int kt) {
+  // Tile staging: global -> LDS directly.  One wave-wide load writes 64 consecutive
+  // 16-byte chunks (RPL rows) of the stage; each lane fetches the global chunk that
+  // belongs at its swizzled LDS position.  Rows past the end of the operand are
+  // clamped to its last row (they only feed outputs that are never stored).
+  constexpr int WAVES = WM * WN;
+  constexpr int NLA = BM / RPL / WAVES, NLB = BN / RPL / WAVES;      // wave-loads per wave and k-tile
+  static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "tile/waves mismatch");
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  uint32_t offa[NLA], offb[NLB];
+  {
+    const int rl = lane / CPR, pc = lane % CPR;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int c = tid + i * NT, row = c >> 3, cc = c & 7;
-      const int64_t gr = m0 + row;
-      ra[i] = (gr < g.m) ? *reinterpret_cast<const uint4*>(A + (size_t)gr * g.lda + (size_t)kt * BK + cc * 8)
-                         : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < NLA; ++i) {
+      const int row = (wave_u + WAVES * i) * RPL + rl;
+      int64_t gr = m0 + row;
+      if (gr > g.m - 1) gr = g.m - 1;
+      offa[i] = (uint32_t)(gr * g.lda) + ((pc ^ ((row >> SW_SHIFT) & (CPR - 1))) << 3);
     }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int c = tid + i * NT, row = c >> 3, cc = c & 7;
-      const int gn = n0 + row;
-      rb[i] = (gn < g.n) ? *reinterpret_cast<const uint4*>(W + (size_t)gn * g.k + (size_t)kt * BK + cc * 8)
-                         : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < NLB; ++i) {
+      const int row = (wave_u + WAVES * i) * RPL + rl;
+      int gn = n0 + row;
+      if (gn > g.n - 1) gn = g.n - 1;
+      offb[i] = (uint32_t)gn * (uint32_t)g.k + ((pc ^ ((row >> SW_SHIFT) & (CPR - 1))) << 3);
     }
-  };
-  auto store_tiles = [&](int buf) {
+  }
+  auto load_tiles = [&](int kt, int buf) {
     uint8_t* sa = smem + buf * STAGE;
     uint8_t* sb = sa + A_BYTES;
+    const uint16_t* ak = A + (size_t)kt * BK;
+    const uint16_t* wk = W + (size_t)kt * BK;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int c = tid + i * NT, row = c >> 3, cc = c & 7;
-      *reinterpret_cast<uint4*>(sa + row * 128 + ((cc ^ (row & 7)) << 4)) = ra[i];
-    }
+    for (int i = 0; i < NLA; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ak + offa[i]), (lptr_t)(sa + (wave_u + WAVES * i) * 1024), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const int c = tid + i * NT, row = c >> 3, cc = c & 7;
-      *reinterpret_cast<uint4*>(sb + row * 128 + ((cc ^ (row & 7)) << 4)) = rb[i];
-    }
+    for (int i = 0; i < NLB; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(wk + offb[i]), (lptr_t)(sb + (wave_u + WAVES * i) * 1024), 16, 0, 0);
   };
 
   f32x16 acc[MI][NI];
@@ -90,14 +113,28 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
+  // NSTAGE-deep ring of LDS stages: tile kt+NSTAGE-1 is requested while tile kt is
+  // multiplied.  Loads of one wave complete in order, so "all but the newest
+  // (NSTAGE-2) tiles have landed" is a vmcnt threshold of (NSTAGE-2)*(NLA+NLB).
   const int nk = g.k / BK;
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
+#pragma unroll
+  for (int st = 0; st < NSTAGE - 1; ++st)
+    if (st < nk) load_tiles(st, st);
   const int lr = lane & 31, lg = lane >> 5;
+  int buf = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_tiles(kt + 1);
-    const uint8_t* sa = smem + (kt & 1) * STAGE;
+    if (NSTAGE == 3 && kt + 1 < nk) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLA + NLB) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();       // tile kt visible to all waves; stage of tile kt-1 no longer read by anyone
+    if (kt + NSTAGE - 1 < nk) {
+      int nb = buf + NSTAGE - 1;
+      if (nb >= NSTAGE) nb -= NSTAGE;
+      load_tiles(kt + NSTAGE - 1, nb);
+    }
+    const uint8_t* sa = smem + buf * STAGE;
     const uint8_t* sb = sa + A_BYTES;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
@@ -106,12 +143,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
         const int row = wm * TM + mi * 32 + lr;
-        af[mi] = *reinterpret_cast<const bf16x8*>(sa + row * 128 + ((ch ^ (row & 7)) << 4));
+        af[mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
       }
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
         const int row = wn * TN + ni * 32 + lr;
-        bfr[ni] = *reinterpret_cast<const bf16x8*>(sb + row * 128 + ((ch ^ (row & 7)) << 4));
+        bfr[ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
       }
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
@@ -119,70 +156,104 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmArgs g) {
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tiles((kt + 1) & 1);
-    __syncthreads();
+    if (++buf == NSTAGE) buf = 0;
   }
 
-  // ---- epilogue: lane holds row (lane & 31) and columns 8*(v/4) + 4*(lane>>5) + v%4 of each 32x32 tile
+  // ---- epilogue.  In the accumulator a lane holds row (lane & 31) and columns
+  // 8*(v/4) + 4*(lane>>5) + v%4 of each 32x32 tile: writing that to a row-major matrix
+  // directly would touch 32 cache lines per store instruction.  Each wave therefore
+  // passes its sub-tile through a private LDS buffer, 32 rows at a time, and comes
+  // back with lanes running along the row (16 bytes per lane): stores and the fp32
+  // residual read-modify-write are full contiguous segments.  Only the transposed-V
+  // part of the QKV projection keeps the register layout (there consecutive lanes =
+  // consecutive tokens is exactly the contiguous direction).
+  constexpr int EPS = TN + 4;                      // padded row stride of the staging buffer (floats)
+  static_assert(WAVES * 32 * EPS * 4 <= NSTAGE * STAGE, "epilogue staging does not fit in the operand stages");
+  static_assert(256 % TN == 0 && TN % 4 == 0, "wave tile width");
+  constexpr int LPR = TN / 4;                      // lanes per row when reading back
+  constexpr int RPP = 64 / LPR;                    // rows per read pass
+  __syncthreads();                                 // every wave is done with the operand stages
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPS);
+  const int wcol0 = n0 + wn * TN;
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int64_t row = m0 + wm * TM + mi * 32 + lr;
-    if (row >= g.m) continue;
-    int64_t dst = row;
-    int pi = 0, vc = 0;
-    if (EPI == EPI_EMBED) {
-      if (g.dst_row) dst = g.dst_row[row];
-      if (g.pos_idx) pi = g.pos_idx[row];
+    const int64_t rbase = m0 + wm * TM + mi * 32;
+    if (EPI == EPI_QKV && wcol0 + TN > g.split) {
+      // transposed-V columns straight from registers
+      const int64_t row = rbase + lr;
+      if (row < g.m) {
+        const int vc = g.vcol[row];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int col = wcol0 + ni * 32 + 8 * vq + 4 * lg;
+            if (col >= g.split && col < g.n) {
+              float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+              if (g.bias) b4 = *reinterpret_cast<const float4*>(g.bias + col);
+              uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
+              vt[0] = f32_to_bf16(acc[mi][ni][4 * vq] + b4.x);
+              vt[g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 1] + b4.y);
+              vt[2 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 2] + b4.z);
+              vt[3 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 3] + b4.w);
+            }
+          }
+      }
+      if (wcol0 >= g.split) continue;              // nothing else in this wave tile
     }
-    if (EPI == EPI_QKV) vc = g.vcol[row];
+    // registers -> LDS (lane = row)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int col = n0 + wn * TN + ni * 32 + 8 * vq + 4 * lg;
-        if (col >= g.n) continue;
-        float4 val = make_float4(acc[mi][ni][4 * vq], acc[mi][ni][4 * vq + 1], acc[mi][ni][4 * vq + 2],
-                                 acc[mi][ni][4 * vq + 3]);
-        if (g.bias) {
-          const float4 b4 = *reinterpret_cast<const float4*>(g.bias + col);
-          val.x += b4.x; val.y += b4.y; val.z += b4.z; val.w += b4.w;
+      for (int vq = 0; vq < 4; ++vq)
+        *reinterpret_cast<float4*>(ep + lr * EPS + ni * 32 + 8 * vq + 4 * lg) =
+            make_float4(acc[mi][ni][4 * vq], acc[mi][ni][4 * vq + 1], acc[mi][ni][4 * vq + 2], acc[mi][ni][4 * vq + 3]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same-wave LDS ops complete in order; keep the compiler from reordering
+    // LDS -> global (lanes along the row)
+    const int c4 = (lane % LPR) * 4;
+    const int col = wcol0 + c4;
+    float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (g.bias && col < g.n) b4 = *reinterpret_cast<const float4*>(g.bias + col);
+#pragma unroll
+    for (int ps = 0; ps < 32 / RPP; ++ps) {
+      const int r = ps * RPP + lane / LPR;
+      const int64_t row = rbase + r;
+      float4 val = *reinterpret_cast<const float4*>(ep + r * EPS + c4);
+      if (row >= g.m || col >= g.n) continue;
+      val.x += b4.x; val.y += b4.y; val.z += b4.z; val.w += b4.w;
+      if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
+        if (EPI == EPI_QKV && col >= g.split) continue;
+        if (EPI == EPI_GELU) {
+          val.x = gelu_fast(val.x); val.y = gelu_fast(val.y); val.z = gelu_fast(val.z); val.w = gelu_fast(val.w);
         }
-        if (EPI == EPI_STORE || EPI == EPI_GELU || (EPI == EPI_QKV && col < g.split)) {
-          if (EPI == EPI_GELU) {
-            val.x = gelu_fast(val.x); val.y = gelu_fast(val.y); val.z = gelu_fast(val.z); val.w = gelu_fast(val.w);
-          }
-          uint2 pk;
-          pk.x = pack_bf16x2(val.x, val.y);
-          pk.y = pack_bf16x2(val.z, val.w);
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
-        } else if (EPI == EPI_RESID) {
-          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
-          float4 old = *c;
-          old.x += val.x; old.y += val.y; old.z += val.z; old.w += val.w;
-          *c = old;
-        } else if (EPI == EPI_EMBED) {
-          if (g.pos_kind == 1) {
-            const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)pi * g.n + col);
-            val.x += p0.x; val.y += p0.y; val.z += p0.z; val.w += p0.w;
-          } else if (g.pos_kind == 2) {
-            const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)(pi & 0xFFFF) * g.n + col);
-            const float4 p1 = *reinterpret_cast<const float4*>(g.pos1 + (size_t)(pi >> 16) * g.n + col);
-            val.x += p0.x + p1.x; val.y += p0.y + p1.y; val.z += p0.z + p1.z; val.w += p0.w + p1.w;
-          }
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col) = val;
-        } else if (EPI == EPI_QKV) {
-          uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
-          vt[0] = f32_to_bf16(val.x);
-          vt[g.ldvt] = f32_to_bf16(val.y);
-          vt[2 * g.ldvt] = f32_to_bf16(val.z);
-          vt[3 * g.ldvt] = f32_to_bf16(val.w);
+        uint2 pk;
+        pk.x = pack_bf16x2(val.x, val.y);
+        pk.y = pack_bf16x2(val.z, val.w);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
+      } else if (EPI == EPI_RESID) {
+        float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
+        float4 old = *c;
+        old.x += val.x; old.y += val.y; old.z += val.z; old.w += val.w;
+        *c = old;
+      } else if (EPI == EPI_EMBED) {
+        const int pi = g.pos_idx ? g.pos_idx[row] : 0;
+        if (g.pos_kind == 1) {
+          const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)pi * g.n + col);
+          val.x += p0.x; val.y += p0.y; val.z += p0.z; val.w += p0.w;
+        } else if (g.pos_kind == 2) {
+          const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)(pi & 0xFFFF) * g.n + col);
+          const float4 p1 = *reinterpret_cast<const float4*>(g.pos1 + (size_t)(pi >> 16) * g.n + col);
+          val.x += p0.x + p1.x; val.y += p0.y + p1.y; val.z += p0.z + p1.z; val.w += p0.w + p1.w;
         }
+        const int64_t dst = g.dst_row ? (int64_t)g.dst_row[row] : row;
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col) = val;
       }
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next block overwrites the buffer
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, int MINB>
 static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
   const int tiles_n = (a.n + BN - 1) / BN;
   const int64_t tiles_m = (a.m + BM - 1) / BM;
@@ -190,11 +261,11 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
   if (total <= 0) return hipSuccess;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-  const size_t lds = 2 * (size_t)(BM + BN) * 128;
+  const size_t lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
   dim3 block(WM * WN * 64);
 #define TCMV_GEMM_CASE(E)                                                                              \
   case E: {                                                                                            \
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, E>;                                                   \
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, NSTAGE, MINB, E>;                                 \
     if (lds > 64 * 1024) {                                                                             \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                          \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);        \
@@ -216,14 +287,17 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   if (a.m == 0 || a.n == 0) return hipSuccess;
   if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return hipErrorInvalidValue;
   if (a.epi == EPI_QKV && (a.split % 4)) return hipErrorInvalidValue;
-  static const int big = []{ const char* e = getenv("TCMV_GEMM_BIG"); return e ? atoi(e) : 0; }();
-  if (big == 1) return launch_cfg<256, 256, 2, 2>(a, s);
-  if (big == 2) return launch_cfg<256, 128, 2, 2>(a, s);
-  if (big == 3) return launch_cfg<256, 256, 2, 4>(a, s);
-  if (big == 4) return launch_cfg<256, 256, 4, 2>(a, s);
-  if (big == 5) return launch_cfg<128, 256, 2, 2>(a, s);
-  if (big == 6) return launch_cfg<256, 128, 4, 2>(a, s);
-  return launch_cfg<128, 128, 2, 2>(a, s);
+  // operand element offsets are kept in 32 bits
+  if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return hipErrorInvalidValue;
+  static const int forced = [] { const char* e = getenv("TCMV_GEMM_TILE"); return e ? atoi(e) : 0; }();
+  // 256x256 tiles (8 waves, one workgroup per CU) when there are at least two full rounds of
+  // them and the output is wide or the contraction long; 128x128 tiles (4 waves, two
+  // workgroups per CU) otherwise.  (Measured on the encoder's shapes.)
+  const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
+  const int cfg = forced ? forced : ((big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560)) ? 3 : 1);
+  if (cfg == 2) return launch_cfg<256, 128, 2, 2, 32, 3, 2>(a, s);
+  if (cfg == 3) return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+  return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
 }
 
 }  // namespace tcmv

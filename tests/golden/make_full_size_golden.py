@@ -42,12 +42,14 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--out", default=None)
+    ap.add_argument("--workers", type=int, default=1, help="threads over attention heads (arithmetic unchanged)")
     args = ap.parse_args()
     t0 = time.time()
     wl = workloads.full_config(args.config)
     print(f"[{time.time() - t0:7.1f}s] generated {wl.name}", flush=True)
     dt = np.float64 if args.config == 1 else np.float32
-    res = oracle.run(wl, dtype=dt, progress=lambda l: print(f"[{time.time() - t0:7.1f}s] layer {l} done", flush=True))
+    res = oracle.run(wl, dtype=dt, progress=lambda l: print(f"[{time.time() - t0:7.1f}s] layer {l} done", flush=True),
+                     workers=args.workers)
     m2 = wl.desc.merge ** 2 if wl.desc.out_dim else 1
     final = res["out"] if wl.desc.out_dim else res["hidden"]
     rows = sample_rows(res["cu_seqlens"], final.shape[0], m2)

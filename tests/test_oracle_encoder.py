@@ -251,3 +251,10 @@ def test_row_subset_evaluation_equals_full_evaluation():
     full = oe.encoder_block(x, cu, desc, w, 0)
     part = oe.encoder_block(x, cu, desc, w, 0, rows=rows)
     assert np.abs(full[rows] - part).max() <= 1e-13
+
+
+def test_threaded_heads_give_identical_results():
+    rng = np.random.default_rng(31)
+    q, k, v = _rand(rng, 50, 48), _rand(rng, 50, 48), _rand(rng, 50, 48)
+    cu = [0, 13, 50]
+    assert np.array_equal(oe.attention(q, k, v, cu, 4), oe.attention(q, k, v, cu, 4, workers=3))
