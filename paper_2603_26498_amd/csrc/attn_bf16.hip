@@ -37,6 +37,7 @@ namespace tcmv {
 namespace {
 constexpr int BKV = 64;
 constexpr int NTHREADS = 256;
+constexpr int kStages = 3;          // LDS ring: tile t (V still in use), tile t+1 (K in use), tile t+2 (in flight)
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 }  // namespace
@@ -70,7 +71,7 @@ template <int DH, int NT>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
   constexpr int WQ = 32 * NT;             // query rows per wave
-  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::STAGE];
+  __shared__ __attribute__((aligned(16))) uint8_t smem[kStages * C::STAGE];
 
   const int total = a.n_work * a.heads;
   const int chunk = (total + 7) >> 3;
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 
   // padding rows of the V^T tiles: ones row (denominator) then zeros
   if (C::DHP > DH) {
-    for (int i = tid; i < 2 * (C::DHP - DH) * (BKV / 2); i += NTHREADS) {
+    for (int i = tid; i < kStages * (C::DHP - DH) * (BKV / 2); i += NTHREADS) {
       const int buf = i / ((C::DHP - DH) * (BKV / 2));
       const int rem = i - buf * ((C::DHP - DH) * (BKV / 2));
       const int row = DH + rem / (BKV / 2), c2 = rem % (BKV / 2);
@@ -163,11 +164,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 
   const int n_tiles = (w.seg_len + BKV - 1) / BKV;
   const bool ragged = (w.seg_len % BKV) != 0;
-  load_tile(0, 0, ragged && n_tiles == 1);
-  wait_tile();
-  __syncthreads();
 
-  // S^T block: 32 keys (block kb of the staged tile) x 32*NT queries
+  // ---- building blocks -------------------------------------------------------------
+  // S^T block: 32 keys (block kb of a staged tile) x 32*NT queries
   auto score_block = [&](const uint8_t* sk, int kb, f32x16 (&s)[NT]) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -181,13 +180,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
         s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][ks], s[nt], 0, 0, 0);
     }
   };
-  // online softmax of one block (per lane = per query column); returns packed probabilities.
-  // The running reference m_run only moves when the block maximum exceeds it by more than
-  // kLazy (in log2 units): probabilities may then exceed 1 (by at most 2^kLazy), which
-  // changes nothing mathematically because numerator and denominator share the reference,
-  // and it makes the rescaling of O rare.
+  // Statistics of a finished score block (per lane = per query column): mask the ragged
+  // tail, take the block maximum and decide whether the softmax reference has to move.
+  // The reference m_run only moves when the block maximum exceeds it by more than kLazy
+  // (in log2 units): probabilities may then exceed 1 (by at most 2^kLazy), which changes
+  // nothing mathematically because numerator and denominator share the reference, and it
+  // makes the rescaling of O rare.  Branches live here, outside the interleaved region.
   constexpr float kLazy = 8.0f;
-  auto softmax_block = [&](f32x16 (&s)[NT], bf16x8 (&pf)[NT][2], int key0, bool mask) {
+  auto stats_block = [&](f32x16 (&s)[NT], int key0, bool mask) {
     if (mask) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
@@ -210,22 +210,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
       alpha[nt] = move ? __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs) : 1.0f;
       m_run[nt] = m_new;
       need_rescale = need_rescale || move;
-      const float mc = m_new * cs;
-      float psum = 0.f;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        uint32_t pk[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[nt][8 * j + 2 * e], cs, -mc));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[nt][8 * j + 2 * e + 1], cs, -mc));
-          if (!C::ONES) psum += p0 + p1;
-          pk[e] = pack_bf16x2(p0, p1);
-        }
-        uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        pf[nt][j] = __builtin_bit_cast(bf16x8, u);
-      }
-      if (!C::ONES) l_run[nt] = l_run[nt] * alpha[nt] + psum;
+      if (!C::ONES) l_run[nt] *= alpha[nt];
     }
     if (__any(need_rescale)) {
 #pragma unroll
@@ -236,40 +221,101 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
           for (int v = 0; v < 16; ++v) o[mt][nt][v] *= alpha[nt];
     }
   };
-  // O^T += V^T P^T for the 32 keys of block kb (two k-steps of 16 keys)
-  auto pv_block = [&](const uint8_t* sv, int kb, const bf16x8 (&pf)[NT][2]) {
+  // O^T += V^T P^T for k-step j (16 keys) of block kb
+  auto pv_step = [&](const uint8_t* sv, int kb, int j, const bf16x8 (&pf)[NT]) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int mt = 0; mt < C::MT; ++mt) {
+      const int row = mt * 32 + lr;
+      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ ((row >> 1) & 7)) << 4));
 #pragma unroll
-      for (int mt = 0; mt < C::MT; ++mt) {
-        const int row = mt * 32 + lr;
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ ((row >> 1) & 7)) << 4));
+      for (int nt = 0; nt < NT; ++nt)
+        o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt], o[mt][nt], 0, 0, 0);
+    }
+  };
+  // One branch-free region: the score MFMAs of the NEXT 32-key block, the exponentials of
+  // the CURRENT block and the PV MFMAs of the current block.  The MFMA is asynchronous but
+  // issue is in order: a clump of MFMAs would block the vector instructions behind it.  The
+  // scheduling groups below ask for one score MFMA, then a slice of the exponential work
+  // (fma / exp2 / pack), repeatedly; the PV MFMAs follow and run under the statistics code
+  // of the next block.
+  auto region = [&](const uint8_t* sk_next, int kb_next, f32x16 (&s_next)[NT], const f32x16 (&s_cur)[NT],
+                    const uint8_t* sv_cur, int kb_cur) {
+    constexpr int n_s = C::KS * NT;               // score MFMAs
+    bf16x8 pf[NT][2];
+    float mc[NT], psum[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][j], o[mt][nt], 0, 0, 0);
+    for (int nt = 0; nt < NT; ++nt) { mc[nt] = m_run[nt] * cs; psum[nt] = 0.f; }
+    score_block(sk_next, kb_next, s_next);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        uint32_t pk[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float a0 = __builtin_amdgcn_exp2f(fmaf(s_cur[nt][8 * j + 2 * e], cs, -mc[nt]));
+          const float a1 = __builtin_amdgcn_exp2f(fmaf(s_cur[nt][8 * j + 2 * e + 1], cs, -mc[nt]));
+          if (!C::ONES) psum[nt] += a0 + a1;
+          pk[e] = pack_bf16x2(a0, a1);
+        }
+        const uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        pf[nt][j] = __builtin_bit_cast(bf16x8, u);
       }
+      if (!C::ONES) l_run[nt] += psum[nt];
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      bf16x8 pj[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) pj[nt] = pf[nt][j];
+      pv_step(sv_cur, kb_cur, j, pj);
+    }
+    // per score MFMA: (16*NT exps, 16*NT fma, 8*NT pack) / n_s instructions of each kind, rounded up
+    constexpr int tr = (16 * NT + n_s - 1) / n_s;
+    constexpr int va = (24 * NT + n_s - 1) / n_s;
+    __builtin_amdgcn_sched_group_barrier(0x100, C::KS, 0);            // K fragments
+#pragma unroll
+    for (int i = 0; i < n_s; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, va, 0);             // vector ALU slice
+      __builtin_amdgcn_sched_group_barrier(0x400, tr, 0);             // transcendental slice
+    }
   };
 
-  // Software pipeline over 32-key blocks: the score MFMAs of the next block are issued
-  // before the softmax arithmetic of the current one, so the matrix pipe and the vector
-  // ALU of one wave overlap:   S(t,1) || softmax(t,0) ;  PV(t,0) || softmax(t,1) ;  PV(t,1).
+  // ---- pipeline ---------------------------------------------------------------------
+  // LDS ring of three stages.  At the barrier of iteration t: tile t+1 has landed (its
+  // loads were issued one iteration earlier), every wave is done with tile t-1, so tile
+  // t+2 can be requested into that stage.
+  load_tile(0, 0, ragged && n_tiles == 1);
+  if (n_tiles > 1) load_tile(1, 1, ragged && n_tiles == 2);
+  // tile 0 (the older one) has landed once at most a tile's worth of loads is outstanding; waves
+  // issue NW/4 or NW/4+1 loads per tile, so the smaller count is the safe threshold for all
+  if (n_tiles > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NW / 4) : "memory");
+  else wait_tile();
+  __syncthreads();
   f32x16 s0[NT], s1[NT];
   score_block(smem, 0, s0);
+  stats_block(s0, 0, ragged && n_tiles == 1);
+  int st = 0;                                     // stage of tile t
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * BKV;
-    if (t + 1 < n_tiles) load_tile(t + 1, (t + 1) & 1, ragged && (t + 2 == n_tiles));
-    const uint8_t* sk = smem + (t & 1) * C::STAGE;
+    const int st1 = (st + 1 == kStages) ? 0 : st + 1;
+    const int st2 = (st1 + 1 == kStages) ? 0 : st1 + 1;
+    const uint8_t* sk = smem + st * C::STAGE;
     const uint8_t* sv = sk + C::K_BYTES;
     const bool mask_tile = ragged && t + 1 == n_tiles;
-    bf16x8 p0[NT][2], p1[NT][2];
-    score_block(sk, 1, s1);
-    softmax_block(s0, p0, j0, mask_tile);
-    pv_block(sv, 0, p0);
-    softmax_block(s1, p1, j0 + 32, mask_tile);
-    pv_block(sv, 1, p1);
+    // block 0 of tile t: exp + PV, while block 1's scores are computed
+    region(sk, 1, s1, s0, sv, 0);
+    stats_block(s1, j0 + 32, mask_tile);
+    // tile t+1 must be visible, tile t-1 is free
     wait_tile();
     __syncthreads();
-    if (t + 1 < n_tiles) score_block(smem + ((t + 1) & 1) * C::STAGE, 0, s0);
+    if (t + 2 < n_tiles) load_tile(t + 2, st2, ragged && (t + 3 == n_tiles));
+    // block 1 of tile t: exp + PV, while block 0 of tile t+1 is scored (for the last tile the
+    // extra score block reads a stale stage; its result is never used)
+    region(smem + st1 * C::STAGE, 0, s0, s1, sv, 1);
+    if (t + 1 < n_tiles) stats_block(s0, j0 + BKV, ragged && t + 2 == n_tiles);
+    st = st1;
   }
 
   // ---- normalise and store: lane holds query (lane & 31), head-dim rows 8*(v/4) + 4*lg + v%4
