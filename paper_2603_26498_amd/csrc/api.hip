@@ -38,12 +38,14 @@ struct tcmv_plan {
   std::vector<int32_t> cls_rows;
   std::vector<AttnWork> work;
   std::vector<float> lut;             // [3][256]
+  std::vector<PreStrip> strips;       // preprocessing work of requests that are copied line by line
+  std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
   int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
   int n_segments = 0;
   // device copy (allocated on first device use)
   uint8_t* d_meta = nullptr;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
-         off_cls = 0, off_work = 0, off_lut = 0, meta_bytes = 0;
+         off_cls = 0, off_work = 0, off_lut = 0, off_strips = 0, off_run_rows = 0, meta_bytes = 0;
 };
 
 namespace {
@@ -61,8 +63,6 @@ int fail_hip(tcmv_ctx* ctx, hipError_t e, const char* what) {
 // query rows per attention work item on the bf16 path: two query tiles per wave
 // where the register file allows it (head size up to 80), one otherwise
 int attn_bq_bf16(int dh) {
-  static const int forced = [] { const char* e = getenv("TCMV_ATTN_BQ"); return e ? atoi(e) : 0; }();
-  if (forced == 128 || forced == 256) return forced;
   return dh <= 80 ? 256 : 128;
 }
 
@@ -162,6 +162,8 @@ int ensure_uploaded(tcmv_ctx* ctx, tcmv_plan* p) {
   put(p->off_cls, p->cls_rows.data(), p->cls_rows.size() * 4);
   put(p->off_work, p->work.data(), p->work.size() * sizeof(AttnWork));
   put(p->off_lut, p->lut.data(), p->lut.size() * 4);
+  put(p->off_strips, p->strips.data(), p->strips.size() * sizeof(PreStrip));
+  put(p->off_run_rows, p->run_rows.data(), p->run_rows.size() * 4);
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_meta), p->meta_bytes);
   if (e != hipSuccess) { p->d_meta = nullptr; return fail_hip(ctx, e, "hipMalloc(plan metadata)"); }
   e = hipMemcpy(p->d_meta, blob.data(), p->meta_bytes, hipMemcpyHostToDevice);
@@ -356,6 +358,21 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     if (p->cu.back() + rows > (1LL << 30)) return bad("too many tokens");
     const int64_t row0 = p->cu.back();
     const int item_idx = (int)p->items.size();
+    di.row0 = (int)p->prow_item.size();
+    {
+      // line-by-line copy needs: no resampling, a compiled strip kernel, 4-byte aligned lines
+      const bool strip_ok = !di.resized && preprocess_has_strip_kernel(d.patch, d.tpatch) &&
+                            (reinterpret_cast<uintptr_t>(it.d_frames) % 4 == 0) && ((int64_t)it.src_w * 3) % 4 == 0 &&
+                            ((int64_t)it.src_h * it.src_w * 3) % 4 == 0;
+      const int64_t n_rows = (int64_t)di.gt * di.gh * di.gw;
+      if (strip_ok) {
+        for (int t = 0; t < di.gt; ++t)
+          for (int ph = 0; ph < di.gh; ++ph)
+            for (int pw0 = 0; pw0 < di.gw; pw0 += kStripTokens) p->strips.push_back(PreStrip{item_idx, t, ph, pw0});
+      } else {
+        for (int64_t r = 0; r < n_rows; ++r) p->run_rows.push_back((int32_t)(di.row0 + r));
+      }
+    }
     if (d.use_cls) p->cls_rows.push_back((int32_t)row0);
     int64_t local = d.use_cls ? 1 : 0;
     auto emit = [&](int t, int h, int w) {
@@ -409,6 +426,8 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->off_cls = place(off, p->cls_rows);
   p->off_work = place(off, p->work);
   p->off_lut = place(off, p->lut);
+  p->off_strips = place(off, p->strips);
+  p->off_run_rows = place(off, p->run_rows);
   p->meta_bytes = off;
   *out = p;
   return TCMV_OK;
@@ -474,6 +493,9 @@ int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) 
   a.patch = ctx->desc.patch; a.tpatch = ctx->desc.tpatch;
   a.k = (int)ctx->k; a.k_pad = (int)ctx->k_pad;
   a.out_bf16 = ctx->desc.dtype == TCMV_BF16;
+  a.merge = ctx->desc.merge;
+  a.strips = dev<PreStrip>(p, p->off_strips); a.n_strips = (int)p->strips.size();
+  a.run_rows = dev<int32_t>(p, p->off_run_rows); a.n_run_rows = (int64_t)p->run_rows.size();
   hipError_t e = timed(ctx, TCMV_K_PREPROCESS, (hipStream_t)stream, [&] { return launch_preprocess(a, (hipStream_t)stream); });
   if (e != hipSuccess) return fail_hip(ctx, e, "preprocess launch");
   return TCMV_OK;

@@ -1,13 +1,22 @@
 // Resize + normalise + patchify in one pass (gfx950).
 //
-// One workgroup produces one patch row (token).  Every output element is decoded
-// to (channel, frame-in-group, patch row, patch column), fetched from the raw
-// uint8 frame (directly, or through a 4-tap integer bilinear resample) and mapped
-// through a 3x256 table of already-rounded normalised values, so the result is
-// bit-exact by construction.  Stores are coalesced: consecutive lanes write
-// consecutive element pairs of the row, padding columns included.
+// A patch row is 3*tpatch*patch runs of `patch` consecutive pixels of one channel of
+// one source line, followed by zero padding.  Two kernels share that decomposition:
+//
+//  * strip kernel (requests whose frames need no resampling): a workgroup takes up to
+//    16 horizontally adjacent patches of one patch line, copies their tpatch*patch
+//    source line segments into LDS with coalesced 4-byte loads (every source byte is
+//    read from HBM exactly once), then each thread produces runs from LDS through a
+//    3x256 table of already-rounded normalised values and writes them so that
+//    consecutive lanes write consecutive addresses of a patch row;
+//  * run kernel (resampled requests, or frames that are not 4-byte aligned): one
+//    thread per run, reading its pixels (or the four bilinear taps of each) straight
+//    from global memory.
+//
+// Integer / table arithmetic only: the result is bit-exact by construction.
 #include "tcmv_internal.h"
 #include "device_utils.h"
+#include <type_traits>
 
 namespace tcmv {
 
@@ -27,86 +36,174 @@ __device__ __forceinline__ void axis_tap(int i, int n_src, int n_dst, int& i0, i
   i0 = a; fr = f;
 }
 
-template <int P_, int TP_>
-__global__ __launch_bounds__(256) void preprocess_kernel(PreprocArgs a) {
+template <int P_, int TP_, bool BF16>
+__global__ __launch_bounds__(256) void preprocess_kernel(PreprocArgs a, int runs_per_row, int data_runs) {
   const int P = P_ ? P_ : a.patch;
   const int TP = TP_ ? TP_ : a.tpatch;
-  const int64_t r = blockIdx.x;
+  __shared__ float lut[768];
+  for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
+  __syncthreads();
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t ri = gid / runs_per_row;                 // index into the list of rows handled here
+  if (ri >= a.n_run_rows) return;
+  const int64_t r = a.run_rows[ri];                      // patch row (token)
+  const int run = (int)(gid - ri * runs_per_row);
+  const int k0 = run * P;                                // first element of the run inside the row
+  typedef typename std::conditional<BF16, uint16_t, float>::type out_t;
+  out_t* out = reinterpret_cast<out_t*>(a.patches) + (size_t)r * a.k_pad + k0;
+  auto emit = [&](int i, float x) {
+    if (BF16) reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)(__float_as_uint(x) >> 16);   // table entries are exact in bf16
+    else reinterpret_cast<float*>(out)[i] = x;
+  };
+  if (run >= data_runs) {                                // padding columns
+    const int n = min(P, a.k_pad - k0);
+    for (int i = 0; i < n; ++i) emit(i, 0.f);
+    return;
+  }
   const int item = a.prow_item[r];
   const int thw = a.prow_thw[r];
   const ItemDev it = a.items[item];
   const int t = thw >> 16, ph = (thw >> 8) & 255, pw = thw & 255;
-
-  __shared__ int tap_r0[kMaxPatch], tap_r1[kMaxPatch], tap_fy[kMaxPatch];
-  __shared__ int tap_c0[kMaxPatch], tap_c1[kMaxPatch], tap_fx[kMaxPatch];
-  if (it.resized) {
-    const int i = threadIdx.x;
-    if (i < P) {
-      axis_tap(ph * P + i, it.src_h, it.dst_h, tap_r0[i], tap_r1[i], tap_fy[i]);
-    } else if (i >= 64 && i < 64 + P) {
-      axis_tap(pw * P + (i - 64), it.src_w, it.dst_w, tap_c0[i - 64], tap_c1[i - 64], tap_fx[i - 64]);
-    }
-    __syncthreads();
-  }
-
-  const size_t frame_stride = (size_t)it.src_h * it.src_w * 3;
+  const int py = run % P;
+  const int tt = (run / P) % TP;
+  const int c = run / (P * TP);
+  const int f = (it.n_frames == 1) ? 0 : t * TP + tt;
+  const uint8_t* fr = it.frames + (size_t)f * it.src_h * it.src_w * 3 + c;
   const int row_stride = it.src_w * 3;
-  const int pp = P * P;
-
-  auto fetch = [&](int k) -> float {
-    if (k >= a.k) return 0.0f;
-    const int px = k % P;
-    const int py = (k / P) % P;
-    const int tt = (k / pp) % TP;
-    const int c = k / (pp * TP);
-    const int f = (it.n_frames == 1) ? 0 : t * TP + tt;
-    const uint8_t* fr = it.frames + (size_t)f * frame_stride + c;
-    int v;
-    if (!it.resized) {
-      v = fr[(size_t)(ph * P + py) * row_stride + (pw * P + px) * 3];
-    } else {
-      const int r0 = tap_r0[py], r1 = tap_r1[py], fy = tap_fy[py];
-      const int c0 = tap_c0[px], c1 = tap_c1[px], fx = tap_fx[px];
-      const uint32_t p00 = fr[(size_t)r0 * row_stride + c0 * 3];
-      const uint32_t p01 = fr[(size_t)r0 * row_stride + c1 * 3];
-      const uint32_t p10 = fr[(size_t)r1 * row_stride + c0 * 3];
-      const uint32_t p11 = fr[(size_t)r1 * row_stride + c1 * 3];
-      const uint32_t acc = p00 * (uint32_t)((kOne - fx) * (kOne - fy)) + p01 * (uint32_t)(fx * (kOne - fy)) +
-                           p10 * (uint32_t)((kOne - fx) * fy) + p11 * (uint32_t)(fx * fy) +
-                           (1u << (2 * kFracBits - 1));
-      v = (int)(acc >> (2 * kFracBits));
-    }
-    return a.lut[c * 256 + v];
-  };
-
-  const int pairs = a.k_pad >> 1;
-  if (a.out_bf16) {
-    uint32_t* out = reinterpret_cast<uint32_t*>(a.patches) + (size_t)r * pairs;
-    for (int k2 = threadIdx.x; k2 < pairs; k2 += 256) {
-      const float x0 = fetch(2 * k2), x1 = fetch(2 * k2 + 1);
-      // table entries are exactly representable in bf16: truncation is exact
-      out[k2] = (__float_as_uint(x0) >> 16) | (__float_as_uint(x1) & 0xFFFF0000u);
-    }
+  const float* lc = lut + c * 256;
+  float x[P_ ? P_ : kMaxPatch];
+  if (!it.resized) {
+    const uint8_t* src = fr + (size_t)(ph * P + py) * row_stride + (size_t)(pw * P) * 3;
+#pragma unroll
+    for (int i = 0; i < (P_ ? P_ : kMaxPatch); ++i)
+      if (i < P) x[i] = lc[src[3 * i]];
   } else {
-    float2* out = reinterpret_cast<float2*>(a.patches) + (size_t)r * pairs;
-    for (int k2 = threadIdx.x; k2 < pairs; k2 += 256) {
-      out[k2] = make_float2(fetch(2 * k2), fetch(2 * k2 + 1));
+    int r0, r1, fy;
+    axis_tap(ph * P + py, it.src_h, it.dst_h, r0, r1, fy);
+    const uint8_t* l0 = fr + (size_t)r0 * row_stride;
+    const uint8_t* l1 = fr + (size_t)r1 * row_stride;
+#pragma unroll
+    for (int i = 0; i < (P_ ? P_ : kMaxPatch); ++i)
+      if (i < P) {
+        int c0, c1, fx;
+        axis_tap(pw * P + i, it.src_w, it.dst_w, c0, c1, fx);
+        const uint32_t p00 = l0[c0 * 3], p01 = l0[c1 * 3], p10 = l1[c0 * 3], p11 = l1[c1 * 3];
+        const uint32_t acc = p00 * (uint32_t)((kOne - fx) * (kOne - fy)) + p01 * (uint32_t)(fx * (kOne - fy)) +
+                             p10 * (uint32_t)((kOne - fx) * fy) + p11 * (uint32_t)(fx * fy) +
+                             (1u << (2 * kFracBits - 1));
+        x[i] = lc[acc >> (2 * kFracBits)];
+      }
+  }
+  if (BF16 && (P_ % 2 == 0) && P_ > 0) {                 // even run length: 4-byte stores of bf16 pairs
+    uint32_t* o2 = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+    for (int i = 0; i < P_ / 2; ++i)
+      o2[i] = (__float_as_uint(x[2 * i]) >> 16) | (__float_as_uint(x[2 * i + 1]) & 0xFFFF0000u);
+  } else {
+#pragma unroll
+    for (int i = 0; i < (P_ ? P_ : kMaxPatch); ++i)
+      if (i < P) emit(i, x[i]);
+  }
+}
+
+// Strip kernel: see the file comment.  Only instantiated for compile-time patch sizes.
+template <int P_, int TP_, bool BF16>
+__global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, int runs_per_row, int data_runs) {
+  constexpr int P = P_ ? P_ : 1, TP = TP_ ? TP_ : 1;
+  constexpr int SEG = kStripTokens * P * 3;              // bytes of one line segment (multiple of 4)
+  static_assert(SEG % 4 == 0, "segment size");
+  __shared__ float lut[768];
+  __shared__ __attribute__((aligned(16))) uint8_t seg[TP * P][SEG];
+  const PreStrip sp = a.strips[blockIdx.x];
+  const ItemDev it = a.items[sp.item];
+  const int ntok = min(kStripTokens, it.gw - sp.pw0);
+  const int nbytes = ntok * P * 3;
+  const bool still = it.n_frames == 1;                   // a still image is its own second frame
+  const int nlines = still ? P : TP * P;
+  const int row_stride = it.src_w * 3;
+  for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
+  // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line
+  const int ndw = nbytes >> 2;
+  for (int i = threadIdx.x; i < nlines * ndw; i += 256) {
+    const int line = i / ndw, dw = i - line * ndw;
+    const int f = still ? 0 : sp.t * TP + line / P;
+    const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+    reinterpret_cast<uint32_t*>(seg[line])[dw] = reinterpret_cast<const uint32_t*>(src)[dw];
+  }
+  const int ntail = nbytes & 3;
+  for (int i = threadIdx.x; i < nlines * ntail; i += 256) {
+    const int line = i / ntail, b = (ndw << 2) + (i - line * ntail);
+    const int f = still ? 0 : sp.t * TP + line / P;
+    const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+    seg[line][b] = src[b];
+  }
+  __syncthreads();
+  // patch row of token (t, ph, pw): raster order, or merge-group-major order
+  const int64_t row_line = (a.merge == 2)
+      ? (int64_t)it.row0 + ((int64_t)(sp.t * (it.gh >> 1) + (sp.ph >> 1)) * (it.gw >> 1)) * 4 + (sp.ph & 1) * 2
+      : (int64_t)it.row0 + (int64_t)(sp.t * it.gh + sp.ph) * it.gw;
+  typedef typename std::conditional<BF16, uint16_t, float>::type out_t;
+  for (int q = threadIdx.x; q < ntok * runs_per_row; q += 256) {
+    const int tok = q / runs_per_row, run = q - tok * runs_per_row;
+    const int pw = sp.pw0 + tok;
+    const int64_t r = (a.merge == 2) ? row_line + (pw >> 1) * 4 + (pw & 1) : row_line + pw;
+    const int k0 = run * P;
+    out_t* out = reinterpret_cast<out_t*>(a.patches) + (size_t)r * a.k_pad + k0;
+    if (run >= data_runs) {                              // padding columns
+      const int n = min(P, a.k_pad - k0);
+      for (int i = 0; i < n; ++i) out[i] = (out_t)0;
+      continue;
+    }
+    const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
+    const uint8_t* src = seg[(still ? 0 : tt) * P + py] + tok * P * 3 + c;
+    const float* lc = lut + c * 256;
+    if (BF16 && P % 2 == 0) {
+      uint32_t* o2 = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+      for (int i = 0; i < P / 2; ++i)
+        o2[i] = (__float_as_uint(lc[src[6 * i]]) >> 16) | (__float_as_uint(lc[src[6 * i + 3]]) & 0xFFFF0000u);
+    } else {
+#pragma unroll
+      for (int i = 0; i < P; ++i) {
+        const float x = lc[src[3 * i]];
+        if (BF16) reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)(__float_as_uint(x) >> 16);
+        else reinterpret_cast<float*>(out)[i] = x;
+      }
     }
   }
 }
 
+template <int P_, int TP_>
+static void launch_pp(const PreprocArgs& a, hipStream_t s) {
+  const int P = a.patch;
+  const int data_runs = 3 * a.tpatch * P;
+  const int runs_per_row = data_runs + (a.k_pad - a.k + P - 1) / P;
+  if (a.n_run_rows > 0) {
+    const int64_t threads = a.n_run_rows * runs_per_row;
+    dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (a.out_bf16) hipLaunchKernelGGL((preprocess_kernel<P_, TP_, true>), grid, block, 0, s, a, runs_per_row, data_runs);
+    else hipLaunchKernelGGL((preprocess_kernel<P_, TP_, false>), grid, block, 0, s, a, runs_per_row, data_runs);
+  }
+  if (a.n_strips > 0 && P_ != 0) {
+    dim3 grid((unsigned)a.n_strips), block(256);
+    if (a.out_bf16) hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, true>), grid, block, 0, s, a, runs_per_row, data_runs);
+    else hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, false>), grid, block, 0, s, a, runs_per_row, data_runs);
+  }
+}
+
+// patch sizes with a compiled strip kernel (the host plans strips only for these)
+bool preprocess_has_strip_kernel(int patch, int tpatch) {
+  return (patch == 14 && (tpatch == 1 || tpatch == 2)) || (patch == 16 && tpatch == 1);
+}
+
 hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s) {
   if (a.rows == 0) return hipSuccess;
-  dim3 grid((unsigned)a.rows), block(256);
-  if (a.patch == 14 && a.tpatch == 2) {
-    hipLaunchKernelGGL((preprocess_kernel<14, 2>), grid, block, 0, s, a);
-  } else if (a.patch == 14 && a.tpatch == 1) {
-    hipLaunchKernelGGL((preprocess_kernel<14, 1>), grid, block, 0, s, a);
-  } else if (a.patch == 16 && a.tpatch == 1) {
-    hipLaunchKernelGGL((preprocess_kernel<16, 1>), grid, block, 0, s, a);
-  } else {
-    hipLaunchKernelGGL((preprocess_kernel<0, 0>), grid, block, 0, s, a);
-  }
+  if (a.n_strips > 0 && !preprocess_has_strip_kernel(a.patch, a.tpatch)) return hipErrorInvalidValue;
+  if (a.patch > kMaxPatch || a.rows * (int64_t)(3 * a.tpatch * a.patch + a.k_pad) > (1LL << 38)) return hipErrorInvalidValue;
+  if (a.patch == 14 && a.tpatch == 2) launch_pp<14, 2>(a, s);
+  else if (a.patch == 14 && a.tpatch == 1) launch_pp<14, 1>(a, s);
+  else if (a.patch == 16 && a.tpatch == 1) launch_pp<16, 1>(a, s);
+  else launch_pp<0, 0>(a, s);
   return hipGetLastError();
 }
 

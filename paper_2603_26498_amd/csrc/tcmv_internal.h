@@ -13,8 +13,13 @@ struct ItemDev {
   int n_frames, src_h, src_w, dst_h, dst_w;
   int gt, gh, gw;          // token grid
   int resized;             // src size differs from dst size
-  int pad_;
+  int row0;                // first patch row of this request
 };
+
+// One unit of preprocessing work for requests that need no resampling: up to
+// kStripTokens horizontally adjacent patches of one patch line of one frame group.
+struct PreStrip { int item, t, ph, pw0; };
+constexpr int kStripTokens = 16;
 
 // One unit of attention work: a tile of query rows of one segment.
 struct AttnWork {
@@ -67,9 +72,13 @@ struct PreprocArgs {
   int64_t rows;
   int patch, tpatch, k, k_pad;
   int out_bf16;
+  int merge;
+  const PreStrip* strips; int n_strips;         // requests copied line by line through LDS
+  const int32_t* run_rows; int64_t n_run_rows;  // patch rows produced run by run (resampled or unaligned requests)
 };
 
 hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s);
+bool preprocess_has_strip_kernel(int patch, int tpatch);
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d,
                             float eps, int out_bf16, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);

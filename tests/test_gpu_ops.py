@@ -199,3 +199,21 @@ def test_empty_inputs_are_no_ops():
     B.tcmv_op_gemm(B.TCMV_BF16, 0, None, None, None, None, 0, 128, 64)
     B.tcmv_op_attention(B.TCMV_BF16, None, [0, 0, 0], 128, 2, None, None, 0)
     sync()
+
+
+def test_gemm_bf16_large_tile_path_with_ragged_rows():
+    """Enough 256x256 tiles to select the large-tile kernel, with a ragged last row tile."""
+    rng = np.random.default_rng(77)
+    m, n, k = 16384 + 37, 2560, 128
+    a = bf16_grid(rng.normal(0, 1, (m, k)))
+    w = bf16_grid(rng.normal(0, 0.05, (n, k)))
+    bias = rng.normal(0, 0.5, n).astype(np.float32)
+    for epi in (B.EPI_STORE, B.EPI_GELU, B.EPI_RESID):
+        c0 = rng.normal(0, 1, (m, n)).astype(np.float32)
+        ref = _gemm_ref(a, w, bias, epi, c0)
+        c = dev(c0) if epi == B.EPI_RESID else torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+        B.tcmv_op_gemm(B.TCMV_BF16, epi, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+        sync()
+        got = c.float().cpu().numpy()
+        tol = 1e-4 * max(1.0, np.abs(ref).max()) if epi == B.EPI_RESID else 2 ** -8 * np.abs(ref).max() + 1e-5
+        assert np.abs(got - ref).max() <= tol, epi
