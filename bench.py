@@ -29,6 +29,28 @@ import workloads  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_attention_hbm_traffic.txt).
+# Valid only for the kernel source it was taken with: reported as null once that file changes.
+ATTN_TRAFFIC = {"source_sha256": "6ac4ab7a54da9bc382ce2672606ea55f02f7409572e9da3bfd2bec104530be3b",
+                "workload": "cfg4_video64x448_vit32x1280_proj3584",
+                "fetch_bytes": 935450 * 1024, "write_bytes": 81936 * 1024}
+
+
+def measured_traffic(kernel, workload):
+    if kernel != "attention" or workload != ATTN_TRAFFIC["workload"]:
+        return None
+    import hashlib
+    src = os.path.join(ROOT, "paper_2603_26498_amd", "csrc", "attn_bf16.hip")
+    try:
+        if hashlib.sha256(open(src, "rb").read()).hexdigest() != ATTN_TRAFFIC["source_sha256"]:
+            return None
+    except OSError:
+        return None
+    return {"fetch_bytes": ATTN_TRAFFIC["fetch_bytes"], "write_bytes": ATTN_TRAFFIC["write_bytes"],
+            "total_bytes": ATTN_TRAFFIC["fetch_bytes"] + ATTN_TRAFFIC["write_bytes"],
+            "algorithmic_bytes": 4 * 32768 * 1280 * 2}
+
 
 def algorithmic_flops(desc, cu, n_patch_rows):
     """2*M*N*K counting, unpadded, no work for masked-out cross-segment scores."""
@@ -226,6 +248,7 @@ def main():
         per_launch = by[dom] / (cnt_dom / args.steps)
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(per_launch / avg_s / 1e9, 1),
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None}
+    roof["traffic"] = measured_traffic(dom, wl.name) if args.layers is None else None
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["avg_launch_us"] = round(avg_s * 1e6, 2)
     roof["algorithmic_per_launch"] = per_launch
