@@ -47,9 +47,7 @@ def measured_traffic(kernel, workload):
             return None
     except OSError:
         return None
-    return {"fetch_bytes": ATTN_TRAFFIC["fetch_bytes"], "write_bytes": ATTN_TRAFFIC["write_bytes"],
-            "total_bytes": ATTN_TRAFFIC["fetch_bytes"] + ATTN_TRAFFIC["write_bytes"],
-            "algorithmic_bytes": 4 * 32768 * 1280 * 2}
+    return ATTN_TRAFFIC["fetch_bytes"] + ATTN_TRAFFIC["write_bytes"]
 
 
 def algorithmic_flops(desc, cu, n_patch_rows):
@@ -248,7 +246,11 @@ def main():
         per_launch = by[dom] / (cnt_dom / args.steps)
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(per_launch / avg_s / 1e9, 1),
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "traffic": None}
-    roof["traffic"] = measured_traffic(dom, wl.name) if args.layers is None else None
+    roof["traffic"] = measured_traffic(dom, wl.name) if args.layers is None else None   # HBM bytes per launch
+    if roof["traffic"] is not None:
+        roof["traffic_detail"] = {"fetch_bytes": ATTN_TRAFFIC["fetch_bytes"], "write_bytes": ATTN_TRAFFIC["write_bytes"],
+                                  "algorithmic_bytes": 4 * 32768 * 1280 * 2,
+                                  "source": "profiles/cfg4_attention_hbm_traffic.txt"}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["avg_launch_us"] = round(avg_s * 1e6, 2)
     roof["algorithmic_per_launch"] = per_launch
