@@ -4,9 +4,9 @@
 //
 // Work decomposition: one workgroup (4 waves) = 32*NT*4 query rows of one
 // segment and one head; each wave owns NT tiles of 32 query rows.  K and V^T
-// tiles of 64 keys are staged in LDS by direct global->LDS loads (double
-// buffered, the next tile's loads are in flight during the MFMAs) and shared by
-// the four waves.  Every K / V^T
+// tiles of 64 keys are staged in LDS by direct global->LDS loads (a ring of
+// three stages, the loads of tile t+2 are in flight while tile t is consumed)
+// and shared by the four waves.  Every K / V^T
 // fragment read from LDS feeds NT MFMAs: LDS bandwidth (about 128 B/clk/CU) is
 // the first limit of this kernel, and NT = 2 halves the LDS bytes per FLOP.
 //
@@ -31,6 +31,7 @@
 #include "tcmv_internal.h"
 #include "device_utils.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace tcmv {
 
@@ -166,45 +167,55 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const bool ragged = (w.seg_len % BKV) != 0;
 
   // ---- building blocks -------------------------------------------------------------
-  // S^T block: 32 keys (block kb of a staged tile) x 32*NT queries
-  auto score_block = [&](const uint8_t* sk, int kb, f32x16 (&s)[NT]) {
+  // K fragments (A operand of the score MFMAs) of 32-key block kb of a staged tile; they are
+  // requested one region before their use
+  bf16x8 kf[C::KS];
+  auto k_frags = [&](const uint8_t* sk, int kb) {
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks)
+      kf[ks] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
+  };
+  // S^T block: 32 keys x 32*NT queries from the fragments in kf
+  auto score_block = [&](f32x16 (&s)[NT]) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[nt][v] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + lr) * C::KSTR + (2 * ks + lg) * 16);
+    for (int ks = 0; ks < C::KS; ++ks)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][ks], s[nt], 0, 0, 0);
-    }
+        s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nt][ks], s[nt], 0, 0, 0);
   };
-  // Statistics of a finished score block (per lane = per query column): mask the ragged
-  // tail, take the block maximum and decide whether the softmax reference has to move.
-  // The reference m_run only moves when the block maximum exceeds it by more than kLazy
-  // (in log2 units): probabilities may then exceed 1 (by at most 2^kLazy), which changes
-  // nothing mathematically because numerator and denominator share the reference, and it
-  // makes the rescaling of O rare.  Branches live here, outside the interleaved region.
+  auto mask_block = [&](f32x16 (&s)[NT], int key0) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = key0 + 8 * (v >> 2) + 4 * lg + (v & 3);
+        if (key >= w.seg_len) s[nt][v] = -INFINITY;
+      }
+  };
+  // Statistics of a finished score block (per lane = per query column), branch-free: block
+  // maximum, decision whether the softmax reference has to move, factor for what has been
+  // accumulated so far.  The reference m_run only moves when the block maximum exceeds it
+  // by more than kLazy (in log2 units): probabilities may then exceed 1 (by at most
+  // 2^kLazy), which changes nothing mathematically because numerator and denominator share
+  // the reference, and it makes the rescaling of O rare.  Returns whether this lane's
+  // reference moved.
   constexpr float kLazy = 8.0f;
-  auto stats_block = [&](f32x16 (&s)[NT], int key0, bool mask) {
-    if (mask) {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = key0 + 8 * (v >> 2) + 4 * lg + (v & 3);
-          if (key >= w.seg_len) s[nt][v] = -INFINITY;
-        }
-    }
+  auto stats_block = [&](const f32x16 (&s)[NT], float (&alpha)[NT]) -> bool {
     bool need_rescale = false;
-    float alpha[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       float mx = s[nt][0];
 #pragma unroll
       for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[nt][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      {   // combine the two half-waves (same query, other keys) on the vector ALU, no LDS round trip:
+          // after the swap one result holds the lower half's value in every lane, the other the upper half's
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      }
       const bool move = (mx - m_run[nt]) * cs > kLazy;     // also true for the first block (m_run = -inf)
       const float m_new = move ? mx : m_run[nt];
       alpha[nt] = move ? __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs) : 1.0f;
@@ -212,44 +223,33 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
       need_rescale = need_rescale || move;
       if (!C::ONES) l_run[nt] *= alpha[nt];
     }
-    if (__any(need_rescale)) {
-#pragma unroll
-      for (int mt = 0; mt < C::MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[mt][nt][v] *= alpha[nt];
-    }
+    return need_rescale;
   };
-  // O^T += V^T P^T for k-step j (16 keys) of block kb
-  auto pv_step = [&](const uint8_t* sv, int kb, int j, const bf16x8 (&pf)[NT]) {
+  auto rescale = [&](const float (&alpha)[NT]) {
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) {
-      const int row = mt * 32 + lr;
-      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + row * (BKV * 2) + (((2 * (2 * kb + j) + lg) ^ ((row >> 1) & 7)) << 4));
+    for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt], o[mt][nt], 0, 0, 0);
-    }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[mt][nt][v] *= alpha[nt];
   };
-  // One branch-free region: the score MFMAs of the NEXT 32-key block, the exponentials of
-  // the CURRENT block and the PV MFMAs of the current block.  The MFMA is asynchronous but
-  // issue is in order: a clump of MFMAs would block the vector instructions behind it.  The
-  // scheduling groups below ask for one score MFMA, then a slice of the exponential work
-  // (fma / exp2 / pack), repeatedly; the PV MFMAs follow and run under the statistics code
-  // of the next block.
-  auto region = [&](const uint8_t* sk_next, int kb_next, f32x16 (&s_next)[NT], const f32x16 (&s_cur)[NT],
-                    const uint8_t* sv_cur, int kb_cur) {
-    constexpr int n_s = C::KS * NT;               // score MFMAs
-    bf16x8 pf[NT][2];
+  // One region = one 32-key block of the online softmax, one basic block of code in the
+  // unmasked case: the score MFMAs of the NEXT block (fragments already in kf), the
+  // exponentials of the CURRENT block, its PV MFMAs, the statistics of the next block and the
+  // request of the K fragments for the region after this one.  The MFMA is asynchronous but
+  // issue is in order, so the vector work (fma / exp2 / pack / max) is spread between the
+  // MFMAs by the scheduler (interleaving strategy below) instead of following them in a lump.
+  // The only branch, the rare rescaling of O, is taken by the caller between regions.
+  auto region = [&](auto masked, f32x16 (&s_next)[NT], const f32x16 (&s_cur)[NT], const uint8_t* sv_cur, int kb_cur,
+                    const uint8_t* sk_pref, int kb_pref, bool next_valid, bool next_mask, int next_key0,
+                    float (&alpha)[NT]) -> bool {
     float mc[NT], psum[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { mc[nt] = m_run[nt] * cs; psum[nt] = 0.f; }
-    score_block(sk_next, kb_next, s_next);
+    // probabilities of keys 16j..16j+15 of the current block, packed as the PV B operand
+    auto exp_half = [&](int j, bf16x8 (&pf)[NT]) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int nt = 0; nt < NT; ++nt) {
         uint32_t pk[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -259,33 +259,60 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
           pk[e] = pack_bf16x2(a0, a1);
         }
         const uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        pf[nt][j] = __builtin_bit_cast(bf16x8, u);
+        pf[nt] = __builtin_bit_cast(bf16x8, u);
       }
+    };
+    auto v_frags = [&](int j, bf16x8 (&vf)[C::MT]) {
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        const int row = mt * 32 + lr;
+        vf[mt] = *reinterpret_cast<const bf16x8*>(sv_cur + row * (BKV * 2) + (((2 * (2 * kb_cur + j) + lg) ^ ((row >> 1) & 7)) << 4));
+      }
+    };
+    auto pv = [&](const bf16x8 (&vf)[C::MT], const bf16x8 (&pf)[NT]) {
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt], pf[nt], o[mt][nt], 0, 0, 0);
+    };
+    bf16x8 pf0[NT], pf1[NT], vf0[C::MT], vf1[C::MT];
+    score_block(s_next);
+    exp_half(0, pf0);
+    v_frags(0, vf0);
+    exp_half(1, pf1);
+    pv(vf0, pf0);
+    v_frags(1, vf1);
+    pv(vf1, pf1);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
       if (!C::ONES) l_run[nt] += psum[nt];
+    k_frags(sk_pref, kb_pref);
+    bool need = false;
+    if constexpr (decltype(masked)::value) {
+      if (next_mask) mask_block(s_next, next_key0);
+      if (next_valid) need = stats_block(s_next, alpha);
+    } else {
+      need = stats_block(s_next, alpha);
     }
+    if constexpr (decltype(masked)::value) {
+      __builtin_amdgcn_iglp_opt(3);
+    } else {
+      constexpr int n_mfma = C::KS * NT + 2 * C::MT * NT;
+      constexpr int n_valu = 16 * NT * 3 + 8 * NT + 16 * NT + 24;      // fma, exp2, max / pack / statistics and addresses
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      bf16x8 pj[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) pj[nt] = pf[nt][j];
-      pv_step(sv_cur, kb_cur, j, pj);
+      for (int i = 0; i < n_mfma; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x402, (n_valu + n_mfma - 1) / n_mfma, 0);
+      }
     }
-    // per score MFMA: (16*NT exps, 16*NT fma, 8*NT pack) / n_s instructions of each kind, rounded up
-    constexpr int tr = (16 * NT + n_s - 1) / n_s;
-    constexpr int va = (24 * NT + n_s - 1) / n_s;
-    __builtin_amdgcn_sched_group_barrier(0x100, C::KS, 0);            // K fragments
-#pragma unroll
-    for (int i = 0; i < n_s; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);              // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, va, 0);             // vector ALU slice
-      __builtin_amdgcn_sched_group_barrier(0x400, tr, 0);             // transcendental slice
-    }
+    return need;
   };
 
   // ---- pipeline ---------------------------------------------------------------------
-  // LDS ring of three stages.  At the barrier of iteration t: tile t+1 has landed (its
-  // loads were issued one iteration earlier), every wave is done with tile t-1, so tile
-  // t+2 can be requested into that stage.
+  // LDS ring of three stages.  At the barrier that opens iteration t, tile t+1 has landed (its
+  // loads were issued one iteration earlier) and every wave is done with tile t-1, so tile
+  // t+2 can be requested into that stage; nothing else synchronises the waves.
   load_tile(0, 0, ragged && n_tiles == 1);
   if (n_tiles > 1) load_tile(1, 1, ragged && n_tiles == 2);
   // tile 0 (the older one) has landed once at most a tile's worth of loads is outstanding; waves
@@ -294,29 +321,38 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   else wait_tile();
   __syncthreads();
   f32x16 s0[NT], s1[NT];
-  score_block(smem, 0, s0);
-  stats_block(s0, 0, ragged && n_tiles == 1);
+  {
+    float alpha[NT];
+    k_frags(smem, 0);
+    score_block(s0);
+    k_frags(smem, 1);
+    if (ragged && n_tiles == 1) mask_block(s0, 0);
+    (void)stats_block(s0, alpha);                 // O is still zero: nothing to rescale
+  }
   int st = 0;                                     // stage of tile t
-  for (int t = 0; t < n_tiles; ++t) {
+  // iteration t: block 0 of tile t (scores in s0) and block 1 (scored in the first region);
+  // the second region already scores block 0 of tile t+1.  For the last tile that extra block
+  // comes from a stale stage and is ignored.
+  auto iteration = [&](auto masked, int t) {
     const int j0 = t * BKV;
     const int st1 = (st + 1 == kStages) ? 0 : st + 1;
     const int st2 = (st1 + 1 == kStages) ? 0 : st1 + 1;
-    const uint8_t* sk = smem + st * C::STAGE;
-    const uint8_t* sv = sk + C::K_BYTES;
-    const bool mask_tile = ragged && t + 1 == n_tiles;
-    // block 0 of tile t: exp + PV, while block 1's scores are computed
-    region(sk, 1, s1, s0, sv, 0);
-    stats_block(s1, j0 + 32, mask_tile);
-    // tile t+1 must be visible, tile t-1 is free
+    const uint8_t* sv = smem + st * C::STAGE + C::K_BYTES;
+    const uint8_t* sk1 = smem + st1 * C::STAGE;
     wait_tile();
     __syncthreads();
     if (t + 2 < n_tiles) load_tile(t + 2, st2, ragged && (t + 3 == n_tiles));
-    // block 1 of tile t: exp + PV, while block 0 of tile t+1 is scored (for the last tile the
-    // extra score block reads a stale stage; its result is never used)
-    region(smem + st1 * C::STAGE, 0, s0, s1, sv, 1);
-    if (t + 1 < n_tiles) stats_block(s0, j0 + BKV, ragged && t + 2 == n_tiles);
+    float alpha[NT];
+    bool need = region(masked, s1, s0, sv, 0, sk1, 0, true, ragged && t + 1 == n_tiles, j0 + 32, alpha);
+    if (__builtin_expect(__any(need), 0)) rescale(alpha);
+    need = region(masked, s0, s1, sv, 1, sk1, 1, t + 1 < n_tiles, ragged && t + 2 == n_tiles, j0 + BKV, alpha);
+    if (__builtin_expect(__any(need), 0)) rescale(alpha);
     st = st1;
-  }
+  };
+  // only the last two iterations can meet masked blocks (ragged tail) or the ignored extra block
+  int t = 0;
+  for (; t + 2 < n_tiles; ++t) iteration(std::false_type{}, t);
+  for (; t < n_tiles; ++t) iteration(std::true_type{}, t);
 
   // ---- normalise and store: lane holds query (lane & 31), head-dim rows 8*(v/4) + 4*lg + v%4
 #pragma unroll
