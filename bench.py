@@ -5,7 +5,7 @@ A "step" is one pass of the whole path (preprocess -> encode -> merge/project)
 over one batch of synthetic requests whose raw uint8 frames are already
 resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--per-request]
 
 The default workload is the video configuration (one 64-frame 448x448 video,
 32768 encoder tokens, full bidirectional attention), which is the one the
@@ -150,14 +150,36 @@ def cpu_baseline(wl, cu, n_patch_rows, budget_note=True):
             "parts_s": {k: round(v, 3) for k, v in parts.items()}, "host_cpus": os.cpu_count()}
 
 
+def per_request_timing(enc, wl, steps, warmup):
+    """The same requests submitted one by one (one plan each, no batching across requests):
+    back to back on one stream, and with preprocess(i+1) overlapped with encode(i)."""
+    import torch
+    plans = [enc.plan([it]) for it in wl.items if it.n_frames > 0]
+    res = {"requests": len(plans)}
+    for name, fn in (("sequential_ms", lambda: [enc.run(p) for p in plans]),
+                     ("pipelined_ms", lambda: enc.run_pipelined(plans))):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = round((time.perf_counter() - t0) / steps * 1e3, 3)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--layers", type=int, default=None, help="override depth (not a valid headline number)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-reference timing")
+    ap.add_argument("--per-request", action="store_true",
+                    help="also time the workload as one plan per request, run back to back and with the "
+                         "preprocessing of request i+1 overlapped with the encoding of request i (two streams)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
@@ -267,7 +289,8 @@ def main():
         "config": {"workload": wl.name, "config_index": args.config, "requests": len(wl.items),
                    "frames": n_frames, "encoder_tokens": T, "merged_tokens": int(info.n_out_tokens),
                    "layers": desc.layers, "d": desc.d, "heads": desc.heads, "mlp": desc.mlp,
-                   "out_dim": desc.out_dim, "headline": args.layers is None},
+                   "out_dim": desc.out_dim, "full_depth": args.layers is None,
+                   "headline": args.layers is None and args.config == 4},
         "frames_per_s": round(n_frames / (ms_per_step * 1e-3), 1),
         "merged_tokens_per_s": round(int(info.n_out_tokens) / (ms_per_step * 1e-3), 1),
         "algorithmic_tflop_per_step": round(total_flops / 1e12, 3),
@@ -277,6 +300,8 @@ def main():
         "kernels": kern,
         "roofline": roof,
     }
+    if args.per_request:
+        res["per_request"] = per_request_timing(enc, wl, args.steps, args.warmup)
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(wl, cu, Tp)
     print(json.dumps(res))

@@ -152,6 +152,41 @@ class VisionEncoder:
         B.tcmv_merge_project(self.ctx, plan.handle, hidden, out, workspace, workspace.numel(), _stream_ptr())
         return out
 
+    def run(self, plan: Plan) -> torch.Tensor:
+        """preprocess -> encode -> merge/project (when the model has a projector) on the current stream."""
+        hidden = self.encode(plan, self.preprocess(plan))
+        return self.merge_project(plan, hidden) if self.desc.out_dim else hidden
+
+    def run_pipelined(self, plans: Sequence[Plan], side_stream: Optional[torch.cuda.Stream] = None):
+        """Runs the plans in order; the preprocessing of plan i+1 is enqueued on a second
+        stream (same priority) so that it overlaps the encoding of plan i (preprocess and
+        encode are separate stages of a request, Sec. 2.1).  Only stream and event plumbing
+        lives here; results are identical to calling run() plan by plan."""
+        _require_gpu()
+        main = torch.cuda.current_stream()
+        side = side_stream if side_stream is not None else torch.cuda.Stream(device=self.device)
+        side.wait_stream(main)
+        patches = [None] * len(plans)
+        ready = [torch.cuda.Event() for _ in plans]
+
+        def stage(i):
+            with torch.cuda.stream(side):
+                patches[i] = self.preprocess(plans[i])
+                ready[i].record(side)
+            patches[i].record_stream(main)
+
+        outs = []
+        if plans:
+            stage(0)
+        for i, plan in enumerate(plans):
+            if i + 1 < len(plans):
+                stage(i + 1)
+            main.wait_event(ready[i])
+            hidden = self.encode(plan, patches[i])
+            outs.append(self.merge_project(plan, hidden) if self.desc.out_dim else hidden)
+            patches[i] = None
+        return outs
+
     def close(self):
         if self.ctx is not None:
             B.tcmv_destroy(self.ctx)

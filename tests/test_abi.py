@@ -57,7 +57,7 @@ def _plan(desc, items):
     return enc, enc.plan(items, upload=False)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 def test_plan_matches_reference_token_order(idx):
     wl = workloads.small_config(idx)
     enc, pl = _plan(wl.desc, wl.items)
@@ -93,9 +93,9 @@ def test_plan_matches_reference_token_order(idx):
 
 
 def test_full_size_token_counts():
-    """Plan sizes of the five full workloads (no frames needed on the host)."""
-    expect = {1: 197, 2: 18432, 4: 32768}
-    for idx in (1, 2, 3, 4, 5):
+    """Plan sizes of the full workloads (no frames needed on the host)."""
+    expect = {1: 197, 2: 18432, 4: 32768, 6: 65536}
+    for idx in (1, 2, 3, 4, 5, 6):
         wl = workloads.full_config(idx, with_frames=False, with_weights=False)
         enc, pl = _plan(wl.desc, wl.items)
         cu = oe.cu_seqlens_of(oe.grids_of(wl.items, wl.desc), wl.desc.use_cls)

@@ -37,7 +37,7 @@ def check_patches(wl, ref, patches):
     assert not got[:, k:].any(), "padding columns must be zero"
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("affine", [False, True])
 def test_small_workloads(idx, affine):
     wl = workloads.small_config(idx, random_affine=affine)
@@ -148,3 +148,29 @@ def test_results_are_deterministic_run_to_run():
     a = run_gpu(wl)[4].float().cpu().numpy()
     b = run_gpu(wl)[4].float().cpu().numpy()
     assert np.array_equal(a, b)
+
+
+def test_per_request_pipeline_matches_plan_by_plan_runs():
+    """One plan per request, preprocessing of the next request overlapped with the
+    encoding of the current one on a second stream: outputs must be the ones of
+    running the requests one after the other, and each request's output must be
+    its rows of the batched run (requests do not interact)."""
+    for idx in (5, 6):
+        wl = workloads.small_config(idx)
+        enc = VisionEncoder(wl.desc, wl.weights)
+        plans = [enc.plan([it]) for it in wl.items]
+        seq = [enc.run(p).float().cpu().numpy() for p in plans]
+        for _ in range(2):
+            pip = enc.run_pipelined(plans)
+            torch.cuda.synchronize()
+            for a, b in zip(seq, pip):
+                assert np.array_equal(a, b.float().cpu().numpy())
+        whole = enc.plan(wl.items)
+        out = enc.run(whole).float().cpu().numpy()
+        m2 = wl.desc.merge ** 2
+        r0 = 0
+        for a, plan in zip(seq, plans):
+            assert plan.info.n_out_tokens == a.shape[0] == plan.info.n_tokens // m2
+            assert_tokens_close(out[r0:r0 + a.shape[0]], a, 2e-2, 0.999, f"{wl.name} request rows")
+            r0 += a.shape[0]
+        assert r0 == out.shape[0]

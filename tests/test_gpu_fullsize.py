@@ -40,7 +40,7 @@ def _sample(cu, n, seed):
     return np.array(sorted(pick), np.int64)
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6])
 def test_full_preprocess_bit_exact(idx):
     wl = workloads.full_config(idx, with_weights=False, layers=0)
     wl.weights = workloads.make_weights(wl.desc, 1)
@@ -61,7 +61,7 @@ def test_full_preprocess_bit_exact(idx):
     assert row == pl.info.n_patch_rows
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6])
 def test_full_token_count_one_layer_sampled_rows(idx):
     wl = workloads.full_config(idx, layers=1)
     desc, w = wl.desc, wl.weights

@@ -222,6 +222,29 @@ def test_token_counts_of_the_workloads():
     assert cu[1] == 16384 and cu[2] == 32768 and np.all(np.diff(cu)[26:] == 0) and len(cu) == 227
 
 
+def test_video_as_frames_shares_patch_halves_with_the_video():
+    """Feeding a video frame by frame (Sec. 7.1) repeats every frame over the
+    temporal patch; the video pairs consecutive frames.  So row r of the video's
+    frame pair j holds, in its first temporal slot, what image 2j holds there, and
+    in its second slot what image 2j+1 holds there."""
+    import workloads
+    vid, seq = workloads.small_config(4), workloads.small_config(6)
+    assert len(seq.items) == vid.items[0].n_frames
+    pv = op.preprocess_item(vid.items[0], vid.desc)
+    P, tp = vid.desc.patch, vid.desc.tpatch
+    n = (vid.items[0].dst_h // P) * (vid.items[0].dst_w // P)        # rows per frame pair / per image
+    pv = pv.reshape(-1, n, 3, tp, P * P)
+    for j in range(pv.shape[0]):
+        a = op.preprocess_item(seq.items[2 * j], seq.desc).reshape(n, 3, tp, P * P)
+        b = op.preprocess_item(seq.items[2 * j + 1], seq.desc).reshape(n, 3, tp, P * P)
+        assert np.array_equal(pv[j][:, :, 0], a[:, :, 0]) and np.array_equal(pv[j][:, :, 1], b[:, :, 1])
+        assert np.array_equal(a[:, :, 0], a[:, :, 1])
+    wl = workloads.full_config(6, with_frames=False, with_weights=False)
+    from oracle import encoder
+    cu = encoder.cu_seqlens_of(encoder.grids_of(wl.items, wl.desc), 0)
+    assert len(cu) == 65 and np.all(np.diff(cu) == 1024)
+
+
 def test_bad_shapes_raise():
     with pytest.raises(ValueError):
         op.token_grid(1, 1, 30, 28, 14, 2, 2)

@@ -228,18 +228,33 @@ def config5(n_videos=2, n_images=24, n_text=200, video_frames=32, video_side=448
     return Workload("cfg5_mixed_2video_24image_200text", desc, items)
 
 
-WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005}
+def config6(n_frames=64, side=448, layers=32, with_frames=True, desc=None) -> Workload:
+    """The frames of the config-4 video submitted as a sequence of still images
+    (Sec. 7.1 notes that some models treat a video that way): one request and one
+    attention segment per frame, each frame repeated to fill the temporal patch.
+    Same pixels and same encoder as config 4, twice the tokens, attention confined
+    to 1024-token segments."""
+    desc = desc or qwen_like_desc(layers=layers)
+    rng = np.random.default_rng(3)
+    frames = random_frames(rng, n_frames, side, side) if with_frames else None
+    items = [Item(IMAGE, 1, side, side, side, side, frames[i:i + 1] if with_frames else None)
+             for i in range(n_frames)]
+    return Workload("cfg6_video64x448_as_frames_vit32x1280_proj3584", desc, items)
+
+
+# config 6 runs the config-4 encoder (same weights): only the request structure differs
+WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004}
 
 
 def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> Workload:
-    """The five full-size workloads.  `layers` overrides the depth only."""
+    """The full-size workloads.  `layers` overrides the depth only."""
     kw = {} if layers is None else {"layers": layers}
     if idx == 1:
         wl = config1(with_frames)
         if layers is not None:
             wl.desc.layers = layers
     else:
-        wl = {2: config2, 3: config3, 4: config4, 5: config5}[idx](with_frames=with_frames, **kw)
+        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6}[idx](with_frames=with_frames, **kw)
     if with_weights:
         wl.weights = make_weights(wl.desc, WEIGHT_SEEDS[idx])
     return wl
@@ -267,6 +282,9 @@ def small_config(idx: int, random_affine=True) -> Workload:
         desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
         wl = config5(n_videos=1, n_images=3, n_text=4, video_frames=4, video_side=112, lo=56, hi=196,
                      src_lo=60, src_hi=200, desc=desc)
+    elif idx == 6:
+        desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
+        wl = config6(n_frames=6, side=168, desc=desc)
     else:
         raise ValueError(idx)
     wl.name = f"small{idx}"
