@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtcmv.so")
-SOURCES = ["api.hip", "preprocess.hip", "layernorm.hip", "gemm_bf16.hip", "attn_bf16.hip", "f32_path.hip"]
+SOURCES = ["api.hip", "preprocess.hip", "layernorm.hip", "gemm_bf16.hip", "attn_bf16.hip", "f32_path.hip",
+           "sched.cpp"]    # sched.cpp is host-only code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -36,7 +37,7 @@ def build(verbose: bool = False, jobs: int = 6) -> str:
     hipcc = _hipcc()
 
     def one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)

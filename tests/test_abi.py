@@ -30,6 +30,18 @@ def test_library_exports_every_declared_symbol():
     assert B.error_name(-2) == "TCMV_E_BAD_SHAPE"
 
 
+def test_library_exports_every_scheduler_symbol():
+    from paper_2603_26498_amd import sched_binding as SB
+    hdr = open(os.path.join(ROOT, "include", "tcms.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(tcms_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(SB.SIGNATURES), declared ^ set(SB.SIGNATURES)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert C.sizeof(SB.tcms_cluster_model) == 10 * 8 and C.sizeof(SB.tcms_regulator) == 9 * 8
+
+
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24
     assert C.sizeof(B.tcmv_item) == 6 * 4 + 8
