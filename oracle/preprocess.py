@@ -109,25 +109,40 @@ def token_grid(modality: int, n_frames: int, h: int, w: int, patch: int, tpatch:
     return (gt, h // patch, w // patch)
 
 
-def token_coords(gt: int, gh: int, gw: int, merge: int) -> np.ndarray:
-    """[T, 3] int array: (t, h, w) patch coordinate of every token row, in token order."""
+def token_coords(gt: int, gh: int, gw: int, merge: int, window: int = 0) -> np.ndarray:
+    """[T, 3] int array: (t, h, w) patch coordinate of every token row, in token order.
+    window == 0: per frame group, merge groups in raster order, rows of a group consecutive.
+    window > 0 (a multiple of merge): per frame group, windows of window x window patches in
+    raster order (clipped at the right and bottom edges), the same merge-group order inside
+    each window; every window is then a contiguous run of rows."""
     out = []
-    if merge == 1:
-        for t in range(gt):
-            for h in range(gh):
-                for w in range(gw):
-                    out.append((t, h, w))
-    else:
-        for t in range(gt):
-            for hb in range(gh // merge):
-                for wb in range(gw // merge):
-                    for hi in range(merge):
-                        for wi in range(merge):
-                            out.append((t, hb * merge + hi, wb * merge + wi))
+    if window and window % merge:
+        raise ValueError("window must be a multiple of merge")
+    wh = window if window else max(gh, 1)
+    ww = window if window else max(gw, 1)
+    for t in range(gt):
+        for h0 in range(0, gh, wh):
+            for w0 in range(0, gw, ww):
+                h1, w1 = min(gh, h0 + wh), min(gw, w0 + ww)
+                for hb in range(h0, h1, merge):
+                    for wb in range(w0, w1, merge):
+                        for hi in range(merge):
+                            for wi in range(merge):
+                                out.append((t, hb + hi, wb + wi))
     return np.asarray(out, np.int64).reshape(-1, 3)
 
 
-def patchify(x: np.ndarray, patch: int, tpatch: int, merge: int) -> np.ndarray:
+def window_lengths(gt: int, gh: int, gw: int, window: int):
+    """Number of tokens of every window of one request, in token order."""
+    out = []
+    for _ in range(gt):
+        for h0 in range(0, gh, window):
+            for w0 in range(0, gw, window):
+                out.append((min(gh, h0 + window) - h0) * (min(gw, w0 + window) - w0))
+    return out
+
+
+def patchify(x: np.ndarray, patch: int, tpatch: int, merge: int, window: int = 0) -> np.ndarray:
     """x [n_frames, H, W, 3] (any dtype) -> [T, 3*tpatch*patch*patch].
     A single frame is repeated tpatch times."""
     n, h, w, c = x.shape
@@ -136,7 +151,7 @@ def patchify(x: np.ndarray, patch: int, tpatch: int, merge: int) -> np.ndarray:
         x = np.repeat(x, tpatch, axis=0)
         n = tpatch
     gt, gh, gw = n // tpatch, h // patch, w // patch
-    coords = token_coords(gt, gh, gw, merge)
+    coords = token_coords(gt, gh, gw, merge, window)
     rows = np.empty((coords.shape[0], 3 * tpatch * patch * patch), x.dtype)
     for r, (t, ph, pw) in enumerate(coords):
         blk = x[t * tpatch:(t + 1) * tpatch, ph * patch:(ph + 1) * patch, pw * patch:(pw + 1) * patch, :]
@@ -165,4 +180,4 @@ def preprocess_item(item, desc) -> np.ndarray:
     if (item.src_h, item.src_w) != (item.dst_h, item.dst_w):
         f = resize_bilinear_u8(f, item.dst_h, item.dst_w)
     x = normalise(f, desc.mean, desc.std, desc.dtype)
-    return patchify(x, desc.patch, desc.tpatch, desc.merge)
+    return patchify(x, desc.patch, desc.tpatch, desc.merge, getattr(desc, "window", 0))

@@ -36,12 +36,17 @@ class ModelDesc:
     merge: int = 1               # 1 or 2 (2x2 spatial merge)
     out_dim: int = 0             # 0 = no projector
     use_cls: int = 0
-    pos: str = "none"            # "none" | "learned1d" | "sep2d"
+    pos: str = "none"            # "none" | "learned1d" | "sep2d" | "rope2d"
     max_pos: int = 0             # rows of the position table(s)
     final_ln: int = 0
     ln_eps: float = 1e-6
     mean: tuple = (0.5, 0.5, 0.5)
     std: tuple = (0.5, 0.5, 0.5)
+    norm: str = "layer"          # "layer" | "rms"
+    gated: int = 0               # 1: MLP is silu(x W_gate) * (x W_up), then W_down
+    window: int = 0              # attention window side in patches (0 = none); tokens are then ordered window by window
+    full_every: int = 0          # with windows: layers l with (l+1) % full_every == 0 attend over the whole segment
+    rope_theta: float = 10000.0  # base of the rotary angles (pos == "rope2d")
 
     @property
     def k(self) -> int:
@@ -130,7 +135,8 @@ def make_weights(desc: ModelDesc, seed: int, *, std: float = 0.02,
         w[p + "w_qkv"] = mat(3 * d, d); w[p + "b_qkv"] = bias(3 * d)
         w[p + "w_o"] = mat(d, d); w[p + "b_o"] = bias(d)
         w[p + "ln2_g"] = gamma(d); w[p + "ln2_b"] = bias(d)
-        w[p + "w_1"] = mat(f, d); w[p + "b_1"] = bias(f)
+        f1 = 2 * f if desc.gated else f            # gated MLP: rows [0, f) gate, rows [f, 2f) up
+        w[p + "w_1"] = mat(f1, d); w[p + "b_1"] = bias(f1)
         w[p + "w_2"] = mat(d, f); w[p + "b_2"] = bias(d)
     if desc.final_ln:
         w["lnf_g"] = gamma(d); w["lnf_b"] = bias(d)
