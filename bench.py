@@ -50,8 +50,22 @@ def measured_traffic(kernel, workload):
     return ATTN_TRAFFIC["fetch_bytes"] + ATTN_TRAFFIC["write_bytes"]
 
 
-def algorithmic_flops(desc, cu, n_patch_rows):
-    """2*M*N*K counting, unpadded, no work for masked-out cross-segment scores."""
+def window_segments(desc, items):
+    """Token counts of the attention windows of a windowed model, over all requests."""
+    lens = []
+    W, P = desc.window, desc.patch
+    for it in items:
+        if it.n_frames == 0:
+            continue
+        gt = 1 if it.n_frames == 1 else it.n_frames // desc.tpatch
+        gh, gw = it.dst_h // P, it.dst_w // P
+        one = [(min(gh, h0 + W) - h0) * (min(gw, w0 + W) - w0) for h0 in range(0, gh, W) for w0 in range(0, gw, W)]
+        lens += one * gt
+    return np.asarray(lens, dtype=np.float64)
+
+
+def algorithmic_flops(desc, cu, n_patch_rows, items=None):
+    """2*M*N*K counting, unpadded, no work for masked-out cross-segment (or cross-window) scores."""
     T = int(cu[-1])
     seg = np.diff(np.asarray(cu, dtype=np.float64))
     d, F, L = desc.d, desc.mlp, desc.layers
@@ -59,9 +73,12 @@ def algorithmic_flops(desc, cu, n_patch_rows):
     fl["embed_gemm"] = 2.0 * n_patch_rows * desc.k * d
     fl["qkv_gemm"] = L * 2.0 * T * d * 3 * d
     fl["out_gemm"] = L * 2.0 * T * d * d
-    fl["fc1_gemm"] = L * 2.0 * T * d * F
+    fl["fc1_gemm"] = L * 2.0 * T * d * F * (2 if getattr(desc, "gated", 0) else 1)
     fl["fc2_gemm"] = L * 2.0 * T * d * F
-    fl["attention"] = L * 4.0 * float((seg ** 2).sum()) * d
+    l_win = sum(1 for l in range(L) if desc.window and not (desc.full_every and (l + 1) % desc.full_every == 0))
+    fl["attention"] = (L - l_win) * 4.0 * float((seg ** 2).sum()) * d
+    if l_win:
+        fl["attention"] += l_win * 4.0 * float((window_segments(desc, items) ** 2).sum()) * d
     if desc.out_dim:
         m2 = desc.merge ** 2
         fl["merge_gemm"] = 2.0 * (T / m2) * ((m2 * d) ** 2 + m2 * d * desc.out_dim)
@@ -113,11 +130,12 @@ def cpu_baseline(wl, cu, n_patch_rows, budget_note=True):
     x = rng.normal(0, 1, (rs, desc.d))
     g = lambda n: w["l0." + n].astype(dt)
     t0 = time.perf_counter()
-    h = oe.layernorm(x, g("ln1_g"), g("ln1_b"), desc.ln_eps)
+    h = oe.norm(desc, x, g("ln1_g"), g("ln1_b"))
     qkv = h @ g("w_qkv").T + g("b_qkv")
     x = x + (qkv[:, :desc.d] @ g("w_o").T + g("b_o"))
-    h = oe.layernorm(x, g("ln2_g"), g("ln2_b"), desc.ln_eps)
-    h = oe.gelu(h @ g("w_1").T + g("b_1"))
+    h = oe.norm(desc, x, g("ln2_g"), g("ln2_b"))
+    u = h @ g("w_1").T + g("b_1")
+    h = oe.silu(u[:, :desc.mlp]) * u[:, desc.mlp:] if desc.gated else oe.gelu(u)
     x = x + (h @ g("w_2").T + g("b_2"))
     t_dense = (time.perf_counter() - t0) * (T / rs)
     # -- attention: one head over all segments (every head has the same shape)
@@ -128,6 +146,14 @@ def cpu_baseline(wl, cu, n_patch_rows, budget_note=True):
     t_attn = (time.perf_counter() - t0) * desc.heads
     parts["block_dense_s"] = t_dense
     parts["block_attention_s"] = t_attn
+    l_win = sum(1 for l in range(desc.layers) if oe.layer_is_windowed(desc, l))
+    t_attn_win = 0.0
+    if l_win:   # windowed layers: the same head over the window segments
+        cu_win = oe.window_cu_seqlens_of(oe.grids_of(wl.items, desc), desc)
+        t0 = time.perf_counter()
+        oe.attention(q1, k1, v1, cu_win, 1)
+        t_attn_win = (time.perf_counter() - t0) * desc.heads
+        parts["block_window_attention_s"] = t_attn_win
     t_merge = 0.0
     if desc.out_dim:
         m2 = desc.merge ** 2
@@ -136,7 +162,8 @@ def cpu_baseline(wl, cu, n_patch_rows, budget_note=True):
         oe.merge_project(rng.normal(0, 1, (rs2, desc.d)), desc, w, dt)
         t_merge = (time.perf_counter() - t0) * (T / rs2)
     parts["merge_s"] = t_merge
-    t_total = parts["preprocess_s"] + parts["embed_s"] + desc.layers * (t_dense + t_attn) + t_merge
+    t_total = (parts["preprocess_s"] + parts["embed_s"] + desc.layers * t_dense + (desc.layers - l_win) * t_attn +
+               l_win * t_attn_win + t_merge)
     try:
         from threadpoolctl import threadpool_info
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
@@ -174,7 +201,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--layers", type=int, default=None, help="override depth (not a valid headline number)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-reference timing")
     ap.add_argument("--per-request", action="store_true",
@@ -239,7 +266,7 @@ def main():
                 "merge_project": ev[2].elapsed_time(ev[3])}
 
     ms_per_step = elapsed / args.steps * 1e3
-    fl = algorithmic_flops(desc, cu, Tp)
+    fl = algorithmic_flops(desc, cu, Tp, wl.items)
     by = algorithmic_bytes(desc, wl.items, cu, Tp)
     total_flops = sum(fl.values())
     kern = {}

@@ -42,6 +42,9 @@
  * giving a grid (gt, gh, gw) = (n_frames/tpatch or 1, dst_h/patch, dst_w/patch).
  * merge == 1: rows ordered (t, h, w).  merge == 2: rows ordered
  * (t, h/2, w/2, h%2, w%2) so every 2x2 merge group is four consecutive rows.
+ * With attention windows (tcmv_model_desc.window) the same order is used inside
+ * each window and windows follow each other; tcmv_plan_row_map returns the
+ * (t, h, w) of every row.
  * Inside a patch row element k = ((c*tpatch + tt)*patch + py)*patch + px; rows
  * are zero-padded from K = 3*tpatch*patch^2 to k_pad (see tcmv_k_pad).
  */
@@ -69,7 +72,8 @@ enum {
 };
 
 typedef enum { TCMV_F32 = 0, TCMV_BF16 = 1 } tcmv_dtype;
-typedef enum { TCMV_POS_NONE = 0, TCMV_POS_LEARNED_1D = 1, TCMV_POS_SEPARABLE_2D = 2 } tcmv_pos;
+typedef enum { TCMV_POS_NONE = 0, TCMV_POS_LEARNED_1D = 1, TCMV_POS_SEPARABLE_2D = 2, TCMV_POS_ROTARY_2D = 3 } tcmv_pos;
+typedef enum { TCMV_NORM_LAYER = 0, TCMV_NORM_RMS = 1 } tcmv_norm;
 typedef enum { TCMV_TEXT = 0, TCMV_IMAGE = 1, TCMV_VIDEO = 2 } tcmv_modality;
 
 /* Encoder description.  d % heads == 0; head size d/heads must be a multiple
@@ -86,6 +90,25 @@ typedef struct {
   int final_ln;    /* 1: LayerNorm after the last block                       */
   float ln_eps;
   float mean[3], std[3]; /* per-channel normalisation x = (v/255 - mean)/std  */
+  /* Encoder-family switches (the vision encoders of the paper's Table 1 differ in
+   * these).  All zero = the plain pre-LN block above.  Non-zero values need
+   * TCMV_BF16 and use_cls == 0. */
+  int norm;        /* tcmv_norm: RMSNorm x/sqrt(mean(x^2)+eps)*gamma replaces every
+                      LayerNorm (beta pointers are ignored)                      */
+  int mlp_gated;   /* 1: h = silu(x Wg^T + bg) * (x Wu^T + bu), out = h W_2^T + b_2;
+                      w_1 is then [2*mlp, d] with row 2j = Wg row j and row
+                      2j+1 = Wu row j, b_1 [2*mlp] in the same order             */
+  int window;      /* > 0 (a multiple of merge): token rows are ordered window by
+                      window (window x window patches, clipped at the right and
+                      bottom edges, raster order of windows inside a frame group,
+                      the usual merge-group order inside a window) and layers
+                      attend inside a window                                     */
+  int full_every;  /* with window > 0: layers l with (l+1) % full_every == 0 attend
+                      over the whole segment; 0 = every layer is windowed        */
+  float rope_theta; /* TCMV_POS_ROTARY_2D: element pairs (2p, 2p+1) of every head of q
+                      and k are rotated; the first dh/4 pairs by
+                      h * theta^(-p/(dh/4)), the others by w * theta^(-(p-dh/4)/(dh/4)),
+                      (h, w) = patch coordinate of the token; dh % 4 == 0        */
 } tcmv_model_desc;
 
 /* One request.  Text requests carry no frames (n_frames == 0), produce no
@@ -205,14 +228,16 @@ int tcmv_profile_read(tcmv_ctx *ctx, double *ms, int64_t *launches);
  * dtype selects the bf16 MFMA path or the fp32 path. ---------------------- */
 
 /* y = LN(x) * gamma + beta over the last dimension (biased variance).
- * x [rows, d] fp32; y [rows, d] bf16 (TCMV_BF16) or fp32 (TCMV_F32). */
+ * x [rows, d] fp32; y [rows, d] bf16 (TCMV_BF16) or fp32 (TCMV_F32).
+ * d_beta == NULL selects RMSNorm: y = x / sqrt(mean(x^2) + eps) * gamma. */
 int tcmv_op_layernorm(int dtype, const float *d_x, const float *d_gamma, const float *d_beta,
                       void *d_y, int64_t rows, int d, float eps, void *stream);
 
 /* C = epilogue(A * W^T + bias).  A [m, k], W [n, k], both bf16 (k % 64 == 0,
  * n % 8 == 0) or fp32.  epilogue: 0: store (bf16 / fp32 by dtype);
  * 1: GELU (erf form) then store; 2: d_c is fp32 [m, n] and is incremented
- * (residual add).  bias fp32 [n] or NULL. */
+ * (residual add); 5 (TCMV_BF16 only): gated product, output column j =
+ * silu(column 2j) * column 2j+1, d_c is bf16 [m, n/2].  bias fp32 [n] or NULL. */
 int tcmv_op_gemm(int dtype, int epilogue, const void *d_a, const void *d_w, const float *d_bias,
                  void *d_c, int64_t m, int n, int k, void *stream);
 

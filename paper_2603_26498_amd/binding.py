@@ -10,12 +10,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libtcmv.so")
 
 TCMV_F32, TCMV_BF16 = 0, 1
-TCMV_POS_NONE, TCMV_POS_LEARNED_1D, TCMV_POS_SEPARABLE_2D = 0, 1, 2
+TCMV_POS_NONE, TCMV_POS_LEARNED_1D, TCMV_POS_SEPARABLE_2D, TCMV_POS_ROTARY_2D = 0, 1, 2, 3
+TCMV_NORM_LAYER, TCMV_NORM_RMS = 0, 1
 TCMV_TEXT, TCMV_IMAGE, TCMV_VIDEO = 0, 1, 2
 TCMV_OK = 0
 TCMV_E_INVALID_ARG, TCMV_E_BAD_SHAPE, TCMV_E_WORKSPACE_TOO_SMALL = -1, -2, -3
 TCMV_E_NO_WEIGHTS, TCMV_E_HIP, TCMV_E_UNSUPPORTED = -4, -5, -6
-EPI_STORE, EPI_GELU, EPI_RESID = 0, 1, 2
+EPI_STORE, EPI_GELU, EPI_RESID, EPI_GATED = 0, 1, 2, 5
 
 LAYER_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 
@@ -24,7 +25,9 @@ class tcmv_model_desc(C.Structure):
     _fields_ = [("dtype", C.c_int), ("layers", C.c_int), ("d", C.c_int), ("heads", C.c_int), ("mlp", C.c_int),
                 ("patch", C.c_int), ("tpatch", C.c_int), ("merge", C.c_int), ("out_dim", C.c_int),
                 ("use_cls", C.c_int), ("pos", C.c_int), ("max_pos", C.c_int), ("final_ln", C.c_int),
-                ("ln_eps", C.c_float), ("mean", C.c_float * 3), ("std", C.c_float * 3)]
+                ("ln_eps", C.c_float), ("mean", C.c_float * 3), ("std", C.c_float * 3),
+                ("norm", C.c_int), ("mlp_gated", C.c_int), ("window", C.c_int), ("full_every", C.c_int),
+                ("rope_theta", C.c_float)]
 
 
 class tcmv_item(C.Structure):
@@ -106,13 +109,16 @@ def error_name(code: int) -> str:
 
 
 def make_desc(dtype="bf16", layers=0, d=0, heads=1, mlp=0, patch=14, tpatch=1, merge=1, out_dim=0, use_cls=0,
-              pos="none", max_pos=0, final_ln=0, ln_eps=1e-6, mean=(0.5, 0.5, 0.5), std=(0.5, 0.5, 0.5)):
+              pos="none", max_pos=0, final_ln=0, ln_eps=1e-6, mean=(0.5, 0.5, 0.5), std=(0.5, 0.5, 0.5),
+              norm="layer", gated=0, window=0, full_every=0, rope_theta=10000.0):
     m = tcmv_model_desc()
     m.dtype = {"f32": TCMV_F32, "bf16": TCMV_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
     m.layers, m.d, m.heads, m.mlp = layers, d, heads, mlp
     m.patch, m.tpatch, m.merge, m.out_dim = patch, tpatch, merge, out_dim
     m.use_cls = use_cls
-    m.pos = {"none": 0, "learned1d": 1, "sep2d": 2}[pos] if isinstance(pos, str) else int(pos)
+    m.pos = {"none": 0, "learned1d": 1, "sep2d": 2, "rope2d": 3}[pos] if isinstance(pos, str) else int(pos)
+    m.norm = {"layer": 0, "rms": 1}[norm] if isinstance(norm, str) else int(norm)
+    m.mlp_gated, m.window, m.full_every, m.rope_theta = int(gated), int(window), int(full_every), float(rope_theta)
     m.max_pos, m.final_ln, m.ln_eps = max_pos, final_ln, ln_eps
     for i in range(3):
         m.mean[i] = mean[i]

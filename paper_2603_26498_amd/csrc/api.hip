@@ -37,6 +37,11 @@ struct tcmv_plan {
   std::vector<int32_t> row_vcol;      // hidden row -> column in the transposed-V buffer
   std::vector<int32_t> cls_rows;
   std::vector<AttnWork> work;
+  // windowed layers: the windows are the attention segments (own work list and transposed-V columns)
+  std::vector<int32_t> row_vcol_win;
+  std::vector<AttnWork> work_win;
+  int64_t t_vpad_win = 0;
+  std::vector<float> rope;            // [n_tokens][dh]: (cos, sin) of every element pair of a head
   std::vector<float> lut;             // [3][256]
   std::vector<PreStrip> strips;       // preprocessing work of requests that are copied line by line
   std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
@@ -45,7 +50,9 @@ struct tcmv_plan {
   // device copy (allocated on first device use)
   uint8_t* d_meta = nullptr;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
-         off_cls = 0, off_work = 0, off_lut = 0, off_strips = 0, off_run_rows = 0, meta_bytes = 0;
+         off_cls = 0, off_work = 0, off_lut = 0, off_strips = 0, off_run_rows = 0, off_vcol_win = 0, off_work_win = 0,
+         off_rope = 0, meta_bytes = 0;
+  int64_t ldvt() const { return std::max(t_vpad, t_vpad_win); }
 };
 
 namespace {
@@ -82,17 +89,26 @@ int validate_desc(const tcmv_model_desc* d, std::string& why) {
   if (d->layers < 0 || d->d <= 0 || d->heads <= 0 || d->mlp <= 0 || d->patch <= 0 || d->tpatch <= 0 ||
       d->out_dim < 0 || d->max_pos < 0) { why = "non-positive size"; return TCMV_E_INVALID_ARG; }
   if (d->merge != 1 && d->merge != 2) { why = "merge must be 1 or 2"; return TCMV_E_INVALID_ARG; }
-  if (d->pos < TCMV_POS_NONE || d->pos > TCMV_POS_SEPARABLE_2D) { why = "unknown position scheme"; return TCMV_E_INVALID_ARG; }
+  if (d->pos < TCMV_POS_NONE || d->pos > TCMV_POS_ROTARY_2D) { why = "unknown position scheme"; return TCMV_E_INVALID_ARG; }
+  if ((d->norm != TCMV_NORM_LAYER && d->norm != TCMV_NORM_RMS) || (d->mlp_gated != 0 && d->mlp_gated != 1) ||
+      d->window < 0 || d->full_every < 0) { why = "bad encoder-family switch"; return TCMV_E_INVALID_ARG; }
+  if (d->window % d->merge) { why = "window must be a multiple of merge"; return TCMV_E_INVALID_ARG; }
+  if (d->pos == TCMV_POS_ROTARY_2D && !(d->rope_theta > 0.f && std::isfinite(d->rope_theta))) { why = "rope_theta must be positive"; return TCMV_E_INVALID_ARG; }
   if (d->d % d->heads) { why = "d not divisible by heads"; return TCMV_E_INVALID_ARG; }
   if (!(d->ln_eps >= 0.f)) { why = "negative ln_eps"; return TCMV_E_INVALID_ARG; }
   for (int c = 0; c < 3; ++c)
     if (!(d->std[c] > 0.f) || !std::isfinite(d->mean[c])) { why = "bad mean/std"; return TCMV_E_INVALID_ARG; }
-  if (d->pos != TCMV_POS_NONE && d->max_pos <= 0) { why = "position table without rows"; return TCMV_E_INVALID_ARG; }
+  if ((d->pos == TCMV_POS_LEARNED_1D || d->pos == TCMV_POS_SEPARABLE_2D) && d->max_pos <= 0) { why = "position table without rows"; return TCMV_E_INVALID_ARG; }
   if (d->pos == TCMV_POS_SEPARABLE_2D && d->use_cls) { why = "CLS with separable 2-D positions"; return TCMV_E_UNSUPPORTED; }
   if (d->out_dim && d->use_cls) { why = "projector with CLS rows"; return TCMV_E_UNSUPPORTED; }
   if (d->patch > 32) { why = "patch above 32"; return TCMV_E_UNSUPPORTED; }
   if (d->d % 4 || d->d > 2048) { why = "d must be a multiple of 4, at most 2048"; return TCMV_E_UNSUPPORTED; }
   const int dh = d->d / d->heads;
+  if (d->norm || d->mlp_gated || d->window || d->pos == TCMV_POS_ROTARY_2D) {
+    if (d->dtype != TCMV_BF16) { why = "RMSNorm, gated MLP, windows and rotary positions need the bf16 path"; return TCMV_E_UNSUPPORTED; }
+    if (d->use_cls) { why = "RMSNorm, gated MLP, windows and rotary positions are defined without CLS rows"; return TCMV_E_UNSUPPORTED; }
+    if (d->pos == TCMV_POS_ROTARY_2D && dh % 4) { why = "rotary positions need a head size that is a multiple of 4"; return TCMV_E_UNSUPPORTED; }
+  }
   if (d->dtype == TCMV_BF16) {
     if (dh != 32 && dh != 64 && dh != 80 && dh != 96) { why = "bf16 head size must be 32, 64, 80 or 96"; return TCMV_E_UNSUPPORTED; }
     if (d->d % 64 || d->mlp % 64 || d->out_dim % 8) { why = "bf16 path needs d, mlp multiples of 64 and out_dim of 8"; return TCMV_E_UNSUPPORTED; }
@@ -120,12 +136,12 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   w.xn = off; off = align_up(off + T * d.d * e, 256);
   if (d.dtype == TCMV_BF16) {
     w.qkv = off; off = align_up(off + T * 2 * d.d * e, 256);
-    w.vt = off; off = align_up(off + (size_t)d.d * p->t_vpad * e, 256);
+    w.vt = off; off = align_up(off + (size_t)d.d * p->ldvt() * e, 256);
   } else {
     w.qkv = off; off = align_up(off + T * 3 * d.d * e, 256);
     w.vt = off;
   }
-  w.h = off; off = align_up(off + T * d.mlp * e, 256);
+  w.h = off; off = align_up(off + T * d.mlp * e, 256);   // gated MLP: the product silu(gate)*up, also [T, mlp]
   w.total = off;
   return w;
 }
@@ -164,6 +180,9 @@ int ensure_uploaded(tcmv_ctx* ctx, tcmv_plan* p) {
   put(p->off_lut, p->lut.data(), p->lut.size() * 4);
   put(p->off_strips, p->strips.data(), p->strips.size() * sizeof(PreStrip));
   put(p->off_run_rows, p->run_rows.data(), p->run_rows.size() * 4);
+  put(p->off_vcol_win, p->row_vcol_win.data(), p->row_vcol_win.size() * 4);
+  put(p->off_work_win, p->work_win.data(), p->work_win.size() * sizeof(AttnWork));
+  put(p->off_rope, p->rope.data(), p->rope.size() * 4);
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_meta), p->meta_bytes);
   if (e != hipSuccess) { p->d_meta = nullptr; return fail_hip(ctx, e, "hipMalloc(plan metadata)"); }
   e = hipMemcpy(p->d_meta, blob.data(), p->meta_bytes, hipMemcpyHostToDevice);
@@ -302,7 +321,7 @@ int tcmv_set_weights(tcmv_ctx* ctx, const tcmv_weights* w) {
   const tcmv_model_desc& d = ctx->desc;
   if (!w->w_pe || !w->b_pe) return fail(ctx, TCMV_E_INVALID_ARG, "w_pe / b_pe missing");
   if (d.use_cls && !w->cls) return fail(ctx, TCMV_E_INVALID_ARG, "cls missing");
-  if (d.pos != TCMV_POS_NONE && !w->pos0) return fail(ctx, TCMV_E_INVALID_ARG, "pos0 missing");
+  if ((d.pos == TCMV_POS_LEARNED_1D || d.pos == TCMV_POS_SEPARABLE_2D) && !w->pos0) return fail(ctx, TCMV_E_INVALID_ARG, "pos0 missing");
   if (d.pos == TCMV_POS_SEPARABLE_2D && !w->pos1) return fail(ctx, TCMV_E_INVALID_ARG, "pos1 missing");
   if (d.layers > 0 && !w->layer) return fail(ctx, TCMV_E_INVALID_ARG, "layer array missing");
   for (int i = 0; i < d.layers * 12; ++i)
@@ -327,7 +346,11 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   if (!p) return fail(ctx, TCMV_E_INVALID_ARG, "out of host memory");
   p->ctx = ctx;
   p->cu.assign(1, 0);
-  std::vector<int64_t> seg_start, seg_len, seg_v0;
+  std::vector<int64_t> seg_start, seg_len, seg_v0, win_start, win_len, win_v0;
+  const int dh_ = d.d / d.heads;
+  std::vector<double> rope_freq;      // theta^(-j/(dh/4)), j < dh/4
+  if (d.pos == TCMV_POS_ROTARY_2D)
+    for (int j = 0; j < dh_ / 4; ++j) rope_freq.push_back(std::pow((double)d.rope_theta, -(double)j / (double)(dh_ / 4)));
   auto bad = [&](const std::string& m) { delete p; return fail(ctx, TCMV_E_BAD_SHAPE, m); };
   for (int i = 0; i < n_items; ++i) {
     const tcmv_item& it = items[i];
@@ -361,7 +384,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     di.row0 = (int)p->prow_item.size();
     {
       // line-by-line copy needs: no resampling, a compiled strip kernel, 4-byte aligned lines
-      const bool strip_ok = !di.resized && preprocess_has_strip_kernel(d.patch, d.tpatch) &&
+      const bool strip_ok = !di.resized && d.window == 0 && preprocess_has_strip_kernel(d.patch, d.tpatch) &&
                             (reinterpret_cast<uintptr_t>(it.d_frames) % 4 == 0) && ((int64_t)it.src_w * 3) % 4 == 0 &&
                             ((int64_t)it.src_h * it.src_w * 3) % 4 == 0;
       const int64_t n_rows = (int64_t)di.gt * di.gh * di.gw;
@@ -383,19 +406,36 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
       if (d.pos == TCMV_POS_LEARNED_1D) pos = (int32_t)local;
       else if (d.pos == TCMV_POS_SEPARABLE_2D) pos = h | (w << 16);
       p->prow_pos.push_back(pos);
+      if (d.pos == TCMV_POS_ROTARY_2D) {
+        for (int ax = 0; ax < 2; ++ax)
+          for (int j = 0; j < dh_ / 4; ++j) {
+            const double ang = (double)(ax == 0 ? h : w) * rope_freq[(size_t)j];
+            p->rope.push_back((float)std::cos(ang));
+            p->rope.push_back((float)std::sin(ang));
+          }
+      }
       ++local;
     };
-    for (int t = 0; t < di.gt; ++t) {
-      if (d.merge == 1) {
-        for (int h = 0; h < di.gh; ++h)
-          for (int w = 0; w < di.gw; ++w) emit(t, h, w);
-      } else {
-        for (int hb = 0; hb < di.gh / 2; ++hb)
-          for (int wb = 0; wb < di.gw / 2; ++wb)
-            for (int hi = 0; hi < 2; ++hi)
-              for (int wi = 0; wi < 2; ++wi) emit(t, 2 * hb + hi, 2 * wb + wi);
-      }
-    }
+    // frame groups; inside one, windows in raster order (one window = the whole grid without
+    // windows); inside a window, merge groups in raster order, the rows of a group consecutive
+    const int wh = d.window ? d.window : di.gh, ww = d.window ? d.window : di.gw;
+    for (int t = 0; t < di.gt; ++t)
+      for (int h0 = 0; h0 < di.gh; h0 += wh)
+        for (int w0 = 0; w0 < di.gw; w0 += ww) {
+          const int h1 = std::min(di.gh, h0 + wh), w1 = std::min(di.gw, w0 + ww);
+          if (d.window) {
+            const int64_t n_win = (int64_t)(h1 - h0) * (w1 - w0);
+            win_start.push_back(row0 + local);
+            win_len.push_back(n_win);
+            win_v0.push_back(p->t_vpad_win);
+            for (int64_t r = 0; r < n_win; ++r) p->row_vcol_win.push_back((int32_t)(p->t_vpad_win + vt_col_in_segment(r)));
+            p->t_vpad_win += (n_win + kVtAlign - 1) / kVtAlign * kVtAlign;
+          }
+          for (int hb = h0; hb < h1; hb += d.merge)
+            for (int wb = w0; wb < w1; wb += d.merge)
+              for (int hi = 0; hi < d.merge; ++hi)
+                for (int wi = 0; wi < d.merge; ++wi) emit(t, hb + hi, wb + wi);
+        }
     seg_start.push_back(row0);
     seg_len.push_back(rows);
     seg_v0.push_back(p->t_vpad);
@@ -408,6 +448,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->n_tokens = p->cu.back();
   p->n_segments = (int)seg_start.size();
   build_work(p->work, seg_start, seg_len, seg_v0, d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads) : kAttnBQ_f32);
+  if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
   for (int c = 0; c < 3; ++c)
@@ -428,6 +469,9 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->off_lut = place(off, p->lut);
   p->off_strips = place(off, p->strips);
   p->off_run_rows = place(off, p->run_rows);
+  p->off_vcol_win = place(off, p->row_vcol_win);
+  p->off_work_win = place(off, p->work_win);
+  p->off_rope = place(off, p->rope);
   p->meta_bytes = off;
   *out = p;
   return TCMV_OK;
@@ -530,7 +574,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
 
   // the padding columns of the transposed-V buffer must read as zeros in every layer
   if (bf)
-    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)d.d * p->t_vpad * 2, s); }), "V^T clear");
+    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)d.d * p->ldvt() * 2, s); }), "V^T clear");
   // patch embedding (+ position), CLS rows
   {
     GemmArgs g{};
@@ -550,23 +594,29 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   for (int l = 0; l < d.layers; ++l) {
     const void* const* L = ctx->layer.data() + (size_t)l * 12;
     auto f = [&](int j) { return reinterpret_cast<const float*>(L[j]); };
-    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s); }), "LN1");
+    const bool windowed = d.window && !(d.full_every && (l + 1) % d.full_every == 0);
+    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s, d.norm); }), "LN1");
     {
       GemmArgs g{};
       g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * d.d; g.k = d.d;
       g.c = qkv; g.epi = EPI_QKV;
-      if (bf) { g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->t_vpad; g.vcol = dev<int32_t>(p, p->off_vcol); }
+      if (bf) {
+        g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->ldvt();
+        g.vcol = dev<int32_t>(p, windowed ? p->off_vcol_win : p->off_vcol);
+        if (d.pos == TCMV_POS_ROTARY_2D) { g.rope = dev<float>(p, p->off_rope); g.rope_dh = dh; }
+      }
       else { g.ldc = 3 * d.d; }
       TCMV_CHECK(timed(ctx, TCMV_K_QKV_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "QKV GEMM");
     }
     {
       AttnArgs a{};
-      a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size();
+      if (windowed) { a.work = dev<AttnWork>(p, p->off_work_win); a.n_work = (int)p->work_win.size(); }
+      else { a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size(); }
       a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = d.d;
-      a.bq = bf ? attn_bq_bf16(dh) : kAttnBQ_f32;
+      a.bq = !bf ? kAttnBQ_f32 : (windowed ? kAttnBQ_window : attn_bq_bf16(dh));
       if (bf) {
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
-        a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->t_vpad;
+        a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->ldvt();
         a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
       } else {
@@ -582,11 +632,12 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       g.epi = EPI_RESID;
       TCMV_CHECK(timed(ctx, TCMV_K_OUT_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "out-proj GEMM");
     }
-    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(6), f(7), xn, T, d.d, d.ln_eps, bf, s); }), "LN2");
+    TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(6), f(7), xn, T, d.d, d.ln_eps, bf, s, d.norm); }), "LN2");
     {
       GemmArgs g{};
-      g.a = xn; g.lda = d.d; g.w = L[8]; g.bias = f(9); g.c = hbuf; g.ldc = d.mlp; g.m = T; g.n = d.mlp; g.k = d.d;
-      g.epi = EPI_GELU;
+      g.a = xn; g.lda = d.d; g.w = L[8]; g.bias = f(9); g.c = hbuf; g.ldc = d.mlp; g.m = T; g.k = d.d;
+      if (d.mlp_gated) { g.n = 2 * d.mlp; g.epi = EPI_GATED; }      // (gate, up) column pairs -> one column of hbuf
+      else { g.n = d.mlp; g.epi = EPI_GELU; }
       TCMV_CHECK(timed(ctx, TCMV_K_FC1_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "fc1 GEMM");
     }
     {
@@ -599,7 +650,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   if (d.final_ln)
     TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] {
                  return launch_layernorm(x, reinterpret_cast<const float*>(ctx->w.lnf_g),
-                                         reinterpret_cast<const float*>(ctx->w.lnf_b), x, T, d.d, d.ln_eps, 0, s); }),
+                                         reinterpret_cast<const float*>(ctx->w.lnf_b), x, T, d.d, d.ln_eps, 0, s, d.norm); }),
                "final LN");
   return TCMV_OK;
 }
@@ -627,7 +678,7 @@ int tcmv_merge_project(tcmv_ctx* ctx, tcmv_plan* p, const void* d_hidden, void* 
   hipError_t e;
   TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] {
                return launch_layernorm(reinterpret_cast<const float*>(d_hidden), reinterpret_cast<const float*>(ctx->w.lnm_g),
-                                       reinterpret_cast<const float*>(ctx->w.lnm_b), y, T, d.d, d.ln_eps, bf, s); }),
+                                       reinterpret_cast<const float*>(ctx->w.lnm_b), y, T, d.d, d.ln_eps, bf, s, d.norm); }),
              "merger LN");
   {
     GemmArgs g{};
@@ -650,21 +701,25 @@ int tcmv_op_layernorm(int dtype, const float* d_x, const float* d_gamma, const f
                       int64_t rows, int d, float eps, void* stream) {
   if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || rows < 0 || d <= 0) return TCMV_E_INVALID_ARG;
   if (rows == 0) return TCMV_OK;
-  if (!d_x || !d_gamma || !d_beta || !d_y) return TCMV_E_INVALID_ARG;
+  if (!d_x || !d_gamma || !d_y) return TCMV_E_INVALID_ARG;
   if (d % 4 || d > 2048) return TCMV_E_UNSUPPORTED;
-  return launch_layernorm(d_x, d_gamma, d_beta, d_y, rows, d, eps, dtype == TCMV_BF16, (hipStream_t)stream) == hipSuccess
+  return launch_layernorm(d_x, d_gamma, d_beta, d_y, rows, d, eps, dtype == TCMV_BF16, (hipStream_t)stream,
+                          d_beta ? 0 : 1) == hipSuccess
              ? TCMV_OK : TCMV_E_HIP;
 }
 
 int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, const float* d_bias, void* d_c,
                  int64_t m, int n, int k, void* stream) {
-  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || epilogue < 0 || epilogue > 2 || m < 0 || n <= 0 || k <= 0)
+  const bool gated = epilogue == EPI_GATED;
+  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || epilogue < 0 || (epilogue > 2 && !gated) || m < 0 || n <= 0 || k <= 0)
     return TCMV_E_INVALID_ARG;
   if (m == 0) return TCMV_OK;
   if (!d_a || !d_w || !d_c) return TCMV_E_INVALID_ARG;
   if (dtype == TCMV_BF16 && (k % 64 || n % 8)) return TCMV_E_UNSUPPORTED;
+  if (gated && dtype != TCMV_BF16) return TCMV_E_UNSUPPORTED;
   GemmArgs g{};
-  g.a = d_a; g.lda = k; g.w = d_w; g.bias = d_bias; g.c = d_c; g.ldc = n; g.m = m; g.n = n; g.k = k; g.epi = epilogue;
+  g.a = d_a; g.lda = k; g.w = d_w; g.bias = d_bias; g.c = d_c; g.ldc = gated ? n / 2 : n; g.m = m; g.n = n; g.k = k;
+  g.epi = epilogue;
   const hipError_t e = dtype == TCMV_BF16 ? launch_gemm_bf16(g, (hipStream_t)stream) : launch_gemm_f32(g, (hipStream_t)stream);
   return e == hipSuccess ? TCMV_OK : TCMV_E_HIP;
 }

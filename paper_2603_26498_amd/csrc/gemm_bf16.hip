@@ -220,8 +220,21 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
       float4 val = *reinterpret_cast<const float4*>(ep + r * EPS + c4);
       if (row >= g.m || col >= g.n) continue;
       val.x += b4.x; val.y += b4.y; val.z += b4.z; val.w += b4.w;
-      if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
+      if (EPI == EPI_GATED) {
+        // columns (col, col+1) and (col+2, col+3) are (gate, up) pairs of output columns col/2 and col/2 + 1
+        const float h0 = val.x / (1.0f + __expf(-val.x)) * val.y;
+        const float h1 = val.z / (1.0f + __expf(-val.z)) * val.w;
+        *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + (col >> 1)) = pack_bf16x2(h0, h1);
+      } else if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
         if (EPI == EPI_QKV && col >= g.split) continue;
+        if (EPI == EPI_QKV && g.rope) {
+          // rotary positions: the lane holds element pairs p and p+1 of one head (col % 4 == 0, head size % 4 == 0)
+          const int p2 = ((col % g.rope_dh) >> 1) * 2;
+          const float4 cs = *reinterpret_cast<const float4*>(g.rope + (size_t)row * g.rope_dh + p2);   // cos, sin, cos, sin
+          const float x0 = val.x, x1 = val.y, x2 = val.z, x3 = val.w;
+          val.x = x0 * cs.x - x1 * cs.y; val.y = x0 * cs.y + x1 * cs.x;
+          val.z = x2 * cs.z - x3 * cs.w; val.w = x2 * cs.w + x3 * cs.z;
+        }
         if (EPI == EPI_GELU) {
           val.x = gelu_fast(val.x); val.y = gelu_fast(val.y); val.z = gelu_fast(val.z); val.w = gelu_fast(val.w);
         }
@@ -275,7 +288,7 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
   }
   switch (a.epi) {
     TCMV_GEMM_CASE(EPI_STORE) TCMV_GEMM_CASE(EPI_GELU) TCMV_GEMM_CASE(EPI_RESID)
-    TCMV_GEMM_CASE(EPI_EMBED) TCMV_GEMM_CASE(EPI_QKV)
+    TCMV_GEMM_CASE(EPI_EMBED) TCMV_GEMM_CASE(EPI_QKV) TCMV_GEMM_CASE(EPI_GATED)
     default: return hipErrorInvalidValue;
   }
 #undef TCMV_GEMM_CASE
@@ -286,6 +299,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   if (a.m == 0 || a.n == 0) return hipSuccess;
   if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return hipErrorInvalidValue;
   if (a.epi == EPI_QKV && (a.split % 4)) return hipErrorInvalidValue;
+  if (a.epi == EPI_QKV && a.rope && (a.rope_dh % 4 || a.rope_dh <= 0)) return hipErrorInvalidValue;
+  if (a.epi == EPI_GATED && (a.ldc % 2)) return hipErrorInvalidValue;
   // operand element offsets are kept in 32 bits
   if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return hipErrorInvalidValue;
   // 256x256 tiles (8 waves, one workgroup per CU) when there are at least two full rounds of

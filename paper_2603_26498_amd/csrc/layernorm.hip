@@ -1,4 +1,4 @@
-// LayerNorm over the last dimension, one wavefront per row (gfx950, wave64).
+// LayerNorm (or RMSNorm) over the last dimension, one wavefront per row (gfx950, wave64).
 //
 // The row (fp32) is read once with 16-byte loads and kept in registers; the
 // mean and the centred sum of squares are reduced across the wave in fp32 (two
@@ -9,7 +9,7 @@
 
 namespace tcmv {
 
-template <int NV, bool OUT_BF16>
+template <int NV, bool OUT_BF16, bool RMS>
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const float* __restrict__ gamma,
                                                         const float* __restrict__ beta, void* y,
                                                         int64_t rows, int d, float eps) {
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const fl
     v[j] = (i < nvec) ? xr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
     s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
   }
-  const float mean = wave_sum(s) / (float)d;
+  const float mean = RMS ? 0.f : wave_sum(s) / (float)d;
   float q = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const fl
   for (int j = 0; j < NV; ++j) {
     const int i = lane + 64 * j;
     if (i < nvec) {
-      const float4 g = g4[i], b = b4[i];
+      const float4 g = g4[i], b = RMS ? make_float4(0.f, 0.f, 0.f, 0.f) : b4[i];
       float4 o;
       o.x = v[j].x * rstd * g.x + b.x;
       o.y = v[j].y * rstd * g.y + b.y;
@@ -61,14 +61,14 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const fl
   }
 }
 
-template <bool OUT_BF16>
+template <bool OUT_BF16, bool RMS>
 static hipError_t launch_ln_t(const float* x, const float* g, const float* b, void* y, int64_t rows, int d, float eps,
                               hipStream_t s) {
   dim3 grid((unsigned)((rows + 3) / 4)), block(256);
   const int nv = (d / 4 + 63) / 64;
 #define TCMV_LN_CASE(N)                                                                                   \
   case N:                                                                                                 \
-    hipLaunchKernelGGL((layernorm_kernel<N, OUT_BF16>), grid, block, 0, s, x, g, b, y, rows, d, eps);     \
+    hipLaunchKernelGGL((layernorm_kernel<N, OUT_BF16, RMS>), grid, block, 0, s, x, g, b, y, rows, d, eps); \
     break;
   switch (nv) {
     TCMV_LN_CASE(1) TCMV_LN_CASE(2) TCMV_LN_CASE(3) TCMV_LN_CASE(4)
@@ -80,10 +80,11 @@ static hipError_t launch_ln_t(const float* x, const float* g, const float* b, vo
 }
 
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d, float eps,
-                            int out_bf16, hipStream_t s) {
+                            int out_bf16, hipStream_t s, int rms) {
   if (rows == 0) return hipSuccess;
   if (d % 4 || d <= 0 || d > 2048) return hipErrorInvalidValue;
-  return out_bf16 ? launch_ln_t<true>(x, g, b, y, rows, d, eps, s) : launch_ln_t<false>(x, g, b, y, rows, d, eps, s);
+  if (rms) return out_bf16 ? launch_ln_t<true, true>(x, g, b, y, rows, d, eps, s) : launch_ln_t<false, true>(x, g, b, y, rows, d, eps, s);
+  return out_bf16 ? launch_ln_t<true, false>(x, g, b, y, rows, d, eps, s) : launch_ln_t<false, false>(x, g, b, y, rows, d, eps, s);
 }
 
 }  // namespace tcmv

@@ -36,7 +36,8 @@ enum Epilogue {
   EPI_GELU = 1,    // C = gelu(acc + bias)
   EPI_RESID = 2,   // C(fp32) += acc + bias
   EPI_EMBED = 3,   // C(fp32)[dst_row[r]] = acc + bias + position term
-  EPI_QKV = 4      // columns < split: C ; columns >= split: transposed-V buffer
+  EPI_QKV = 4,     // columns < split: C ; columns >= split: transposed-V buffer
+  EPI_GATED = 5    // columns come in (gate, up) pairs: C[:, j] = silu(gate_j) * up_j   (C has n/2 columns)
 };
 
 struct GemmArgs {
@@ -50,6 +51,9 @@ struct GemmArgs {
   const int32_t* dst_row; const int32_t* pos_idx; const float* pos0; const float* pos1; int pos_kind;
   // EPI_QKV (bf16 path): q|k columns go to c (ldc), v columns to vt[col - split][vcol[row]]
   int split; void* vt; int64_t ldvt; const int32_t* vcol;
+  // EPI_QKV with rotary positions: rope[row][p] = (cos, sin) of pair p of a head, p < rope_dh/2;
+  // applied to the columns below split (q and k)
+  const float* rope; int rope_dh;
 };
 
 struct AttnArgs {
@@ -79,8 +83,9 @@ struct PreprocArgs {
 
 hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s);
 bool preprocess_has_strip_kernel(int patch, int tpatch);
+// rms != 0: RMSNorm (no mean subtraction, b is not read)
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d,
-                            float eps, int out_bf16, hipStream_t s);
+                            float eps, int out_bf16, hipStream_t s, int rms = 0);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
@@ -96,6 +101,7 @@ hipError_t launch_cls_rows(float* hidden, const int32_t* cls_rows, int n, const 
 
 // Tile sizes the host must know about.
 constexpr int kAttnBQ_f32 = 64;     // query rows per attention workgroup, fp32 path
+constexpr int kAttnBQ_window = 128; // bf16 path, windowed layers (windows are short segments: one query tile per wave)
 constexpr int kVtAlign = 64;        // segment starts in the transposed-V buffer are multiples of this
 
 // Column of key r (row inside its segment) in the transposed-V buffer, relative to the

@@ -56,7 +56,10 @@ class VisionEncoder:
         self.cdesc = B.make_desc(dtype=desc.dtype, layers=desc.layers, d=desc.d, heads=desc.heads, mlp=desc.mlp,
                                  patch=desc.patch, tpatch=desc.tpatch, merge=desc.merge, out_dim=desc.out_dim,
                                  use_cls=desc.use_cls, pos=desc.pos, max_pos=desc.max_pos, final_ln=desc.final_ln,
-                                 ln_eps=desc.ln_eps, mean=desc.mean, std=desc.std)
+                                 ln_eps=desc.ln_eps, mean=desc.mean, std=desc.std,
+                                 norm=getattr(desc, "norm", "layer"), gated=getattr(desc, "gated", 0),
+                                 window=getattr(desc, "window", 0), full_every=getattr(desc, "full_every", 0),
+                                 rope_theta=getattr(desc, "rope_theta", 10000.0))
         self.ctx = B.tcmv_create(self.cdesc)
         self.k_pad = B.tcmv_k_pad(self.cdesc)
         self.device = device
@@ -93,7 +96,12 @@ class VisionEncoder:
         for l in range(d.layers):
             for j, name in enumerate(B.LAYER_FIELDS):
                 key = f"l{l}.{name}"
-                T[key] = self._mat(w[key]) if name.startswith("w_") else self._vec(w[key])
+                a = w[key]
+                if getattr(d, "gated", 0) and name in ("w_1", "b_1"):
+                    # layout the library expects for a gated MLP: gate and up rows interleaved
+                    # (the caller's array has the gate rows first, then the up rows)
+                    a = np.stack([a[:d.mlp], a[d.mlp:]], axis=1).reshape((2 * d.mlp,) + a.shape[1:])
+                T[key] = self._mat(a) if name.startswith("w_") else self._vec(a)
                 arr[l * 12 + j] = T[key].data_ptr()
         self._layer_arr = arr
         cw = B.tcmv_weights()

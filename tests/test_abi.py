@@ -43,7 +43,7 @@ def test_library_exports_every_scheduler_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24
+    assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24 + 4 * 4 + 4
     assert C.sizeof(B.tcmv_item) == 6 * 4 + 8
     assert C.sizeof(B.tcmv_weights) == 14 * 8
 
@@ -69,7 +69,7 @@ def _plan(desc, items):
     return enc, enc.plan(items, upload=False)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
 def test_plan_matches_reference_token_order(idx):
     wl = workloads.small_config(idx)
     enc, pl = _plan(wl.desc, wl.items)
@@ -81,7 +81,7 @@ def test_plan_matches_reference_token_order(idx):
     assert pl.info.k == wl.desc.k and pl.info.k_pad % 2 == 0 and pl.info.k_pad >= wl.desc.k
     thw = pl.row_map(0)
     dst = pl.row_map(1)
-    ref = np.concatenate([op.token_coords(*g, wl.desc.merge) for g in grids if g[0]] or [np.zeros((0, 3), int)])
+    ref = np.concatenate([op.token_coords(*g, wl.desc.merge, wl.desc.window) for g in grids if g[0]] or [np.zeros((0, 3), int)])
     assert np.array_equal(thw >> 16, ref[:, 0]) and np.array_equal((thw >> 8) & 255, ref[:, 1])
     assert np.array_equal(thw & 255, ref[:, 2])
     # destination rows: patch rows in order, skipping one CLS row at the start of each segment
@@ -106,8 +106,8 @@ def test_plan_matches_reference_token_order(idx):
 
 def test_full_size_token_counts():
     """Plan sizes of the full workloads (no frames needed on the host)."""
-    expect = {1: 197, 2: 18432, 4: 32768, 6: 65536}
-    for idx in (1, 2, 3, 4, 5, 6):
+    expect = {1: 197, 2: 18432, 4: 32768, 6: 65536, 7: 32768}
+    for idx in (1, 2, 3, 4, 5, 6, 7):
         wl = workloads.full_config(idx, with_frames=False, with_weights=False)
         enc, pl = _plan(wl.desc, wl.items)
         cu = oe.cu_seqlens_of(oe.grids_of(wl.items, wl.desc), wl.desc.use_cls)

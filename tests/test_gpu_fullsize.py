@@ -40,7 +40,7 @@ def _sample(cu, n, seed):
     return np.array(sorted(pick), np.int64)
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7])
 def test_full_preprocess_bit_exact(idx):
     wl = workloads.full_config(idx, with_weights=False, layers=0)
     wl.weights = workloads.make_weights(wl.desc, 1)
@@ -61,9 +61,14 @@ def test_full_preprocess_bit_exact(idx):
     assert row == pl.info.n_patch_rows
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70])
 def test_full_token_count_one_layer_sampled_rows(idx):
-    wl = workloads.full_config(idx, layers=1)
+    if idx == 70:                      # the windowed family's full-attention layer (rotary positions, 32768 keys)
+        idx = 7
+        wl = workloads.full_config(7, layers=1)
+        wl.desc.full_every = 1
+    else:
+        wl = workloads.full_config(idx, layers=1)
     desc, w = wl.desc, wl.weights
     enc = VisionEncoder(desc, w)
     pl = enc.plan(wl.items)
@@ -79,7 +84,8 @@ def test_full_token_count_one_layer_sampled_rows(idx):
     pats = [oracle.preprocess.preprocess_item(it, desc) for it in wl.items]
     x = oe.embed(pats, grids, desc, w, np.float64)
     del pats
-    ref = oe.encoder_block(x, cu, desc, w, 0, np.float64, rows=rows)
+    rope, cu_win = oe.layout_of(grids, desc)
+    ref = oe.encoder_block(x, cu, desc, w, 0, np.float64, rows=rows, rope=rope, cu_win=cu_win)
     if desc.final_ln:
         ref = oe.layernorm(ref, w["lnf_g"].astype(np.float64), w["lnf_b"].astype(np.float64), desc.ln_eps)
     assert_tokens_close(got, ref, 2e-2, 0.999, f"cfg{idx} one layer")

@@ -217,3 +217,36 @@ def test_gemm_bf16_large_tile_path_with_ragged_rows():
         got = c.float().cpu().numpy()
         tol = 1e-4 * max(1.0, np.abs(ref).max()) if epi == B.EPI_RESID else 2 ** -8 * np.abs(ref).max() + 1e-5
         assert np.abs(got - ref).max() <= tol, epi
+
+
+# ---------------------------------------------------------------- encoder-family variants
+@pytest.mark.parametrize("rows,d", [(3, 320), (1030, 1280), (77, 64)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rmsnorm(rows, d, dtype):
+    rng = np.random.default_rng(rows + d)
+    x = (rng.normal(0.5, 3, (rows, d))).astype(np.float32)
+    g = (1 + rng.normal(0, 0.3, d)).astype(np.float32)
+    ref = oe.rmsnorm(x.astype(np.float64), g.astype(np.float64), 1e-6)
+    y = torch.empty((rows, d), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
+    B.tcmv_op_layernorm(B.TCMV_BF16 if dtype == "bf16" else B.TCMV_F32, dev(x), dev(g), None, y, rows, d, 1e-6)
+    sync()
+    got = y.float().cpu().numpy()
+    tol = 2e-5 if dtype == "f32" else 2 ** -8
+    assert np.abs(got - ref).max() <= tol * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("m,n2,k", [(300, 256, 128), (1029, 1280, 320), (4100, 6912, 1280)])
+def test_gated_epilogue(m, n2, k):
+    """Columns arrive as (gate, up) pairs; the kernel writes silu(gate) * up."""
+    rng = np.random.default_rng(m)
+    a = bf16_grid(rng.normal(0, 1, (m, k)).astype(np.float32))
+    w = bf16_grid(rng.normal(0, 0.08, (n2, k)).astype(np.float32))
+    bias = rng.normal(0, 0.3, n2).astype(np.float32)
+    u = a.astype(np.float64) @ w.astype(np.float64).T + bias
+    ref = oe.silu(u[:, 0::2]) * u[:, 1::2]
+    c = torch.full((m, n2 // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.tcmv_op_gemm(B.TCMV_BF16, B.EPI_GATED, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n2, k)
+    sync()
+    got = c.float().cpu().numpy()
+    assert np.abs(got - ref).max() <= 2 ** -7 * np.abs(ref).max()
+    assert_tokens_close(got, ref, 1e-2, 0.9999, "gated epilogue")

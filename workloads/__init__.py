@@ -248,8 +248,26 @@ def config6(n_frames=64, side=448, layers=32, with_frames=True, desc=None) -> Wo
     return Workload("cfg6_video64x448_as_frames_vit32x1280_proj3584", desc, items)
 
 
+def windowed_desc(layers=32, d=1280, heads=16, mlp=3456, out_dim=3584, window=8, full_every=8) -> ModelDesc:
+    """The encoder family that Table 1 lists as "Custom ViT": RMSNorm, gated MLP, rotary 2-D
+    positions, attention inside windows of window x window patches except every
+    full_every-th layer.  Same patching and merge as the other image/video workloads."""
+    return ModelDesc(dtype="bf16", layers=layers, d=d, heads=heads, mlp=mlp, patch=14, tpatch=2, merge=2,
+                     out_dim=out_dim, use_cls=0, pos="rope2d", max_pos=0, final_ln=0, norm="rms", gated=1,
+                     window=window, full_every=full_every)
+
+
+def config7(n_frames=64, side=448, layers=32, with_frames=True, desc=None) -> Workload:
+    """The config-4 video through the windowed encoder family: 28 of 32 layers attend inside
+    8x8-patch windows (64 tokens), 4 layers over the whole 32768-token video."""
+    desc = desc or windowed_desc(layers=layers)
+    wl = config4(n_frames=n_frames, side=side, with_frames=with_frames, desc=desc)
+    wl.name = "cfg7_video64x448_windowed_vit32x1280_proj3584"
+    return wl
+
+
 # config 6 runs the config-4 encoder (same weights): only the request structure differs
-WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004}
+WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004, 7: 1007}
 
 
 def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> Workload:
@@ -260,7 +278,7 @@ def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> W
         if layers is not None:
             wl.desc.layers = layers
     else:
-        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6}[idx](with_frames=with_frames, **kw)
+        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[idx](with_frames=with_frames, **kw)
     if with_weights:
         wl.weights = make_weights(wl.desc, WEIGHT_SEEDS[idx])
     return wl
@@ -291,6 +309,11 @@ def small_config(idx: int, random_affine=True) -> Workload:
     elif idx == 6:
         desc = qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
         wl = config6(n_frames=6, side=168, desc=desc)
+    elif idx == 7:
+        # the mixed batch (video, images with ragged window edges, text) through the windowed family
+        desc = windowed_desc(layers=4, d=320, heads=4, mlp=640, out_dim=192, window=4, full_every=2)
+        wl = config5(n_videos=1, n_images=3, n_text=2, video_frames=4, video_side=112, lo=56, hi=196,
+                     src_lo=60, src_hi=200, desc=desc)
     else:
         raise ValueError(idx)
     wl.name = f"small{idx}"
