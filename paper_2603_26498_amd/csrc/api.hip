@@ -47,6 +47,7 @@ struct tcmv_plan {
   std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
   int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
   int n_segments = 0;
+  int bq = 0;                         // query rows per attention work item of the full-segment layers
   // device copy (allocated on first device use)
   uint8_t* d_meta = nullptr;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
@@ -67,10 +68,14 @@ int fail_hip(tcmv_ctx* ctx, hipError_t e, const char* what) {
   return fail(ctx, TCMV_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-// query rows per attention work item on the bf16 path: two query tiles per wave
-// where the register file allows it (head size up to 80), one otherwise
-int attn_bq_bf16(int dh) {
-  return dh <= 80 ? 256 : 128;
+// Query rows per attention work item on the bf16 path.  Head sizes up to 80 allow two query
+// tiles per wave (256 rows with 4 waves, 512 with 8); 512-row items stage every K/V tile once per
+// CU instead of twice and are used when rounding the segments up to 512 rows wastes little.
+int attn_bq_bf16(int dh, const std::vector<int64_t>& seg_len) {
+  if (dh > 80) return 128;
+  int64_t rows = 0, padded = 0;
+  for (int64_t n : seg_len) { rows += n; padded += (n + 511) / 512 * 512; }
+  return (rows > 0 && padded * 100 <= rows * 103) ? 512 : 256;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -447,7 +452,8 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->n_patch_rows = (int64_t)p->prow_item.size();
   p->n_tokens = p->cu.back();
   p->n_segments = (int)seg_start.size();
-  build_work(p->work, seg_start, seg_len, seg_v0, d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads) : kAttnBQ_f32);
+  p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads, seg_len) : kAttnBQ_f32;
+  build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
@@ -613,7 +619,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       if (windowed) { a.work = dev<AttnWork>(p, p->off_work_win); a.n_work = (int)p->work_win.size(); }
       else { a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size(); }
       a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = d.d;
-      a.bq = !bf ? kAttnBQ_f32 : (windowed ? kAttnBQ_window : attn_bq_bf16(dh));
+      a.bq = windowed ? kAttnBQ_window : p->bq;
       if (bf) {
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
         a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->ldvt();
@@ -725,7 +731,7 @@ int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, cons
 }
 
 namespace {
-struct OpAttnLayout { size_t vcol, work, vt, total; int64_t t_vpad; int64_t T; };
+struct OpAttnLayout { size_t vcol, work, vt, total; int64_t t_vpad; int64_t T; int bq; };
 OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int heads, std::vector<int32_t>* vcol,
                             std::vector<AttnWork>* work) {
   OpAttnLayout L{};
@@ -740,7 +746,8 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   L.T = n_seg > 0 ? cu[n_seg] : 0;
   L.t_vpad = vp;
   std::vector<AttnWork> wtmp;
-  build_work(wtmp, ss, sl, sv, dtype == TCMV_BF16 ? attn_bq_bf16(d / heads) : kAttnBQ_f32);
+  L.bq = dtype == TCMV_BF16 ? attn_bq_bf16(d / heads, sl) : kAttnBQ_f32;
+  build_work(wtmp, ss, sl, sv, L.bq);
   if (vcol) {
     vcol->assign((size_t)L.T, 0);
     for (size_t s = 0; s < ss.size(); ++s)
@@ -790,7 +797,7 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
   AttnArgs a{};
   a.work = reinterpret_cast<const AttnWork*>(wsb + L.work); a.n_work = (int)work.size();
   a.heads = heads; a.dh = dh; a.t_total = L.T; a.out = d_out; a.ldo = d;
-  a.bq = dtype == TCMV_BF16 ? attn_bq_bf16(dh) : kAttnBQ_f32;
+  a.bq = L.bq;
   hipError_t e;
   if (dtype == TCMV_BF16) {
     const uint16_t* q = reinterpret_cast<const uint16_t*>(d_qkv);

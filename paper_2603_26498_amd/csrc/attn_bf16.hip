@@ -2,11 +2,13 @@
 // scores are never written to memory; softmax statistics are kept per query in
 // fp32 and updated block by block (online softmax).
 //
-// Work decomposition: one workgroup (4 waves) = 32*NT*4 query rows of one
-// segment and one head; each wave owns NT tiles of 32 query rows.  K and V^T
+// Work decomposition: one workgroup (NWV = 4 or 8 waves) = 32*NT*NWV query rows of
+// one segment and one head; each wave owns NT tiles of 32 query rows.  Eight
+// waves share one staged K/V tile stream per CU instead of two workgroups
+// staging the same tiles twice; four waves waste less on short segments.  K and V^T
 // tiles of 64 keys are staged in LDS by direct global->LDS loads (a ring of
 // three stages, the loads of tile t+2 are in flight while tile t is consumed)
-// and shared by the four waves.  Every K / V^T
+// and shared by the waves of the workgroup.  Every K / V^T
 // fragment read from LDS feeds NT MFMAs: LDS bandwidth (about 128 B/clk/CU) is
 // the first limit of this kernel, and NT = 2 halves the LDS bytes per FLOP.
 //
@@ -37,7 +39,7 @@ namespace tcmv {
 
 namespace {
 constexpr int BKV = 64;
-constexpr int NTHREADS = 256;
+constexpr int kThreads4 = 256;
 constexpr int kStages = 3;          // LDS ring: tile t (V still in use), tile t+1 (K in use), tile t+2 (in flight)
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -68,9 +70,11 @@ struct AttnCfg {
 // global load.  Chunks are XOR-swizzled by (row/2)%8: the LDS serves 16 lanes x 16
 // bytes per clock over 64 banks and two 128-byte rows span the banks, so 16
 // consecutive rows reading the same logical chunk land on 16 different bank groups.
-template <int DH, int NT>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
+template <int DH, int NT, int NWV = 4>
+__global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
+  constexpr int NTHREADS = NWV * 64;
+  constexpr int NLD = (C::NW + NWV - 1) / NWV;     // tile loads per wave
   constexpr int WQ = 32 * NT;             // query rows per wave
   __shared__ __attribute__((aligned(16))) uint8_t smem[kStages * C::STAGE];
 
@@ -114,12 +118,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   // wave-wide load writes 64 consecutive 16-byte chunks of LDS (base + lane*16), so each
   // lane fetches the global chunk that belongs at its LDS position: K rows are stored
   // with a padding chunk (odd chunk count per row), V^T chunks at their swizzled position.
-  // The tile is C::NW wave-loads; wave w issues loads w, w+4, w+8, ...
-  uint32_t goff[C::NI];             // element offset of this lane's tile-0 chunk from K (or VT)
+  // The tile is C::NW wave-loads; wave w issues loads w, w+NWV, w+2*NWV, ...
+  uint32_t goff[NLD];             // element offset of this lane's tile-0 chunk from K (or VT)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
-  for (int i = 0; i < C::NI; ++i) {
-    const int n = wave_u + 4 * i;
+  for (int i = 0; i < NLD; ++i) {
+    const int n = wave_u + NWV * i;
     const int L = n * 64 + lane;                       // K part: chunk index incl. padding chunks
     const int rowk = L / C::KROWCH;
     int cck = L - rowk * C::KROWCH;
@@ -133,8 +137,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const uint32_t kstep = (uint32_t)BKV * (uint32_t)a.ldqk;
   auto load_tile = [&](int t, int buf, bool tail) {
 #pragma unroll
-    for (int i = 0; i < C::NI; ++i) {
-      const int n = wave_u + 4 * i;
+    for (int i = 0; i < NLD; ++i) {
+      const int n = wave_u + NWV * i;
       if (n < C::NW) {
         const bool is_k = n < C::KROWCH;
         uint32_t off = goff[i] + (is_k ? (uint32_t)t * kstep : (uint32_t)t * BKV);
@@ -316,8 +320,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   load_tile(0, 0, ragged && n_tiles == 1);
   if (n_tiles > 1) load_tile(1, 1, ragged && n_tiles == 2);
   // tile 0 (the older one) has landed once at most a tile's worth of loads is outstanding; waves
-  // issue NW/4 or NW/4+1 loads per tile, so the smaller count is the safe threshold for all
-  if (n_tiles > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NW / 4) : "memory");
+  // issue NW/NWV or NW/NWV+1 loads per tile, so the smaller count is the safe threshold for all
+  if (n_tiles > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NW / NWV) : "memory");
   else wait_tile();
   __syncthreads();
   f32x16 s0[NT], s1[NT];
@@ -389,15 +393,20 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.n_work * a.heads;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
-  if (a.bq != 128 && a.bq != 256) return hipErrorInvalidValue;
+  if (a.bq != 128 && a.bq != 256 && a.bq != 512) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
 #define TCMV_ATTN_CASE(D)                                                                         \
   case D:                                                                                         \
-    if (a.bq == 256) hipLaunchKernelGGL((attn_bf16_kernel<D, 2>), dim3(grid), dim3(NTHREADS), 0, s, a); \
-    else hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), dim3(grid), dim3(NTHREADS), 0, s, a);       \
+    if (a.bq == 512) hipLaunchKernelGGL((attn_bf16_kernel<D, 2, 8>), dim3(grid), dim3(512), 0, s, a); \
+    else if (a.bq == 256) hipLaunchKernelGGL((attn_bf16_kernel<D, 2>), dim3(grid), dim3(kThreads4), 0, s, a); \
+    else hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), dim3(grid), dim3(kThreads4), 0, s, a);       \
     break;
   switch (a.dh) {
-    TCMV_ATTN_CASE(32) TCMV_ATTN_CASE(64) TCMV_ATTN_CASE(80) TCMV_ATTN_CASE(96)
+    TCMV_ATTN_CASE(32) TCMV_ATTN_CASE(64) TCMV_ATTN_CASE(80)
+    case 96:   // the register file holds one query tile per wave only
+      if (a.bq != 128) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((attn_bf16_kernel<96, 1>), dim3(grid), dim3(kThreads4), 0, s, a);
+      break;
     default: return hipErrorInvalidValue;
   }
 #undef TCMV_ATTN_CASE

@@ -62,7 +62,7 @@ struct AttnArgs {
   void* out; int64_t ldo;
   const AttnWork* work; int n_work;
   int heads, dh;
-  int bq;                                        // query rows per work item the list was built with (bf16: 128 or 256)
+  int bq;                                        // query rows per work item the list was built with (bf16: 128, 256 or 512)
   int64_t t_total;                               // rows of q/k (for clamping)
   float scale;
 };
