@@ -113,7 +113,7 @@ def test_full_size_projector_sampled_rows(idx):
     assert_tokens_close(got, ref, 2e-2, 0.999, f"cfg{idx} projector")
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
 def test_full_depth_against_stored_reference_rows(idx):
     path = os.path.join(GOLD, f"full_cfg{idx}.npz")
     if not os.path.exists(path):
