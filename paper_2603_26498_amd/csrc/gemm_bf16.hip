@@ -304,10 +304,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // operand element offsets are kept in 32 bits
   if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return hipErrorInvalidValue;
   // 256x256 tiles (8 waves, one workgroup per CU) when there are at least two full rounds of
-  // them and the output is wide or the contraction long; 128x128 tiles (4 waves, two
-  // workgroups per CU) otherwise.  (Measured on the encoder's shapes.)
+  // them and the output is wide or the contraction long, or at least four rounds whatever the
+  // shape; 128x128 tiles (4 waves, two workgroups per CU) otherwise.  (Measured on the
+  // encoder's shapes.)
   const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
-  if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560)) return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+  if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560 || big_tiles >= 1024)) return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
   return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
 }
 
