@@ -309,6 +309,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // encoder's shapes.)
   const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
   if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560 || big_tiles >= 1024)) return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+  // a single small request: fewer than 200 tiles of 128x128 leave most CUs idle; 64x64 tiles
+  // (2 waves) quadruple the number of workgroups
+  const int64_t mid_tiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);
+  if (mid_tiles < 200) return launch_cfg<64, 64, 1, 2, 64, 2, 4>(a, s);
   return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
 }
 

@@ -63,7 +63,9 @@ def _gemm_ref(a, w, bias, epi, c0):
 
 
 @pytest.mark.parametrize("m,n,k", [(1, 64, 64), (127, 128, 64), (128, 128, 128), (300, 320, 640), (1000, 1280, 1216),
-                                   (257, 136, 192), (129, 3840, 1280), (2050, 1280, 5120)])
+                                   (257, 136, 192), (129, 3840, 1280), (2050, 1280, 5120),
+                                   # 200..511 tiles of 128x128: the mid-size tile kernel (smaller ones use 64x64 tiles)
+                                   (2050, 1928, 320), (1500, 2560, 128), (3333, 1280, 192)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_GELU, B.EPI_RESID])
 def test_gemm_bf16(m, n, k, epi):
     rng = np.random.default_rng(m + 3 * n + 7 * k + epi)
