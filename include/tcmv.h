@@ -151,6 +151,7 @@ typedef struct {
   int n_items, n_segments;       /* n_segments: items with at least one token         */
 } tcmv_plan_info;
 
+/* major*100 + minor; 110 added the encoder-family fields at the end of tcmv_model_desc. */
 int tcmv_version(void);
 const char *tcmv_error_name(int code);
 

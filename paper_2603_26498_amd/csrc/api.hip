@@ -251,7 +251,7 @@ hipError_t run_gemm(const tcmv_ctx* ctx, const GemmArgs& g, hipStream_t s) {
 
 extern "C" {
 
-int tcmv_version(void) { return 100; }
+int tcmv_version(void) { return 110; }   // 110: tcmv_model_desc gained the encoder-family switches
 
 const char* tcmv_error_name(int code) {
   switch (code) {

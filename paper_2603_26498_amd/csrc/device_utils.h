@@ -29,21 +29,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // GELU, erf form: x/2 * (1 + erf(x / sqrt 2))
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-// GELU for bf16 outputs: erf from the Abramowitz-Stegun rational approximation
-// 7.1.26 (|error| <= 1.5e-7), far below the bf16 rounding of the result, at about
-// a third of the instructions of the library erff.
+// GELU for bf16 outputs.  x * Phi(x) with Phi(x) = 1 / (1 + exp(-p(x))), p an odd polynomial of
+// degree 5 fitted (minimax over [-10, 10]) to the logit of the normal distribution function:
+// |error| of the product <= 2.6e-5, two orders below the bf16 rounding of the result, in 7
+// vector and 2 transcendental instructions.  The polynomial is evaluated on x clamped to
+// [-8, 8] (beyond that Phi is 0 or 1 to 1e-12 and the fitted polynomial would turn over).
 __device__ __forceinline__ float gelu_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  p *= t;
-  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
-  const float erf_abs = fmaf(-p, e, 1.0f);          // erf(|x|/sqrt2)
-  const float half_x = 0.5f * x;
-  return fmaf(fabsf(half_x), erf_abs, half_x);      // x/2 * (1 + sign(x) erf_abs)
+  const float xc = __builtin_amdgcn_fmed3f(x, -8.0f, 8.0f);
+  const float x2 = xc * xc;
+  // -log2(e) * (1.59501577 + 0.07401129 x^2 - 0.00070303 x^4)
+  float t = fmaf(1.0142630e-3f, x2, -1.0677572e-1f);
+  t = fmaf(t, x2, -2.3011213f);
+  const float e = __builtin_amdgcn_exp2f(t * xc);
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 // compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>)
