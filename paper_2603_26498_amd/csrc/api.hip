@@ -42,6 +42,8 @@ struct tcmv_plan {
   std::vector<AttnWork> work_win;
   int64_t t_vpad_win = 0;
   std::vector<float> rope;            // [n_tokens][dh]: (cos, sin) of every element pair of a head
+  std::vector<int32_t> row_seg, row_seg_win;   // hidden row -> index of its segment / window (key-norm table row)
+  int n_windows = 0;
   std::vector<float> lut;             // [3][256]
   std::vector<PreStrip> strips;       // preprocessing work of requests that are copied line by line
   std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
@@ -52,7 +54,7 @@ struct tcmv_plan {
   uint8_t* d_meta = nullptr;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
          off_cls = 0, off_work = 0, off_lut = 0, off_strips = 0, off_run_rows = 0, off_vcol_win = 0, off_work_win = 0,
-         off_rope = 0, meta_bytes = 0;
+         off_rope = 0, off_row_seg = 0, off_row_seg_win = 0, meta_bytes = 0;
   int64_t ldvt() const { return std::max(t_vpad, t_vpad_win); }
 };
 
@@ -131,7 +133,7 @@ int64_t k_pad_of(const tcmv_model_desc& d) {
 
 size_t elt(const tcmv_ctx* c) { return c->desc.dtype == TCMV_BF16 ? 2 : 4; }
 
-struct EncodeWs { size_t xn, qkv, vt, h, total; };
+struct EncodeWs { size_t xn, qkv, vt, h, kmax, kmax_bytes, total; };
 EncodeWs encode_ws(const tcmv_plan* p) {
   const tcmv_model_desc& d = p->ctx->desc;
   const size_t e = elt(p->ctx);
@@ -147,6 +149,9 @@ EncodeWs encode_ws(const tcmv_plan* p) {
     w.vt = off;
   }
   w.h = off; off = align_up(off + T * d.mlp * e, 256);   // gated MLP: the product silu(gate)*up, also [T, mlp]
+  // largest squared key norm per (segment or window, head)
+  w.kmax_bytes = align_up((size_t)std::max(p->n_segments, p->n_windows) * d.heads * 4, 256);
+  w.kmax = off; off += d.dtype == TCMV_BF16 ? w.kmax_bytes : 0;
   w.total = off;
   return w;
 }
@@ -188,6 +193,8 @@ int ensure_uploaded(tcmv_ctx* ctx, tcmv_plan* p) {
   put(p->off_vcol_win, p->row_vcol_win.data(), p->row_vcol_win.size() * 4);
   put(p->off_work_win, p->work_win.data(), p->work_win.size() * sizeof(AttnWork));
   put(p->off_rope, p->rope.data(), p->rope.size() * 4);
+  put(p->off_row_seg, p->row_seg.data(), p->row_seg.size() * 4);
+  put(p->off_row_seg_win, p->row_seg_win.data(), p->row_seg_win.size() * 4);
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_meta), p->meta_bytes);
   if (e != hipSuccess) { p->d_meta = nullptr; return fail_hip(ctx, e, "hipMalloc(plan metadata)"); }
   e = hipMemcpy(p->d_meta, blob.data(), p->meta_bytes, hipMemcpyHostToDevice);
@@ -213,6 +220,7 @@ void build_work(std::vector<AttnWork>& work, const std::vector<int64_t>& seg_sta
       w.seg_start = (int)seg_start[s];
       w.seg_len = (int)seg_len[s];
       w.v0 = (int)seg_v0[s];
+      w.seg = (int)s;
       work.push_back(w);
     }
   }
@@ -433,7 +441,10 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
             win_start.push_back(row0 + local);
             win_len.push_back(n_win);
             win_v0.push_back(p->t_vpad_win);
-            for (int64_t r = 0; r < n_win; ++r) p->row_vcol_win.push_back((int32_t)(p->t_vpad_win + vt_col_in_segment(r)));
+            for (int64_t r = 0; r < n_win; ++r) {
+              p->row_vcol_win.push_back((int32_t)(p->t_vpad_win + vt_col_in_segment(r)));
+              p->row_seg_win.push_back((int32_t)(win_start.size() - 1));
+            }
             p->t_vpad_win += (n_win + kVtAlign - 1) / kVtAlign * kVtAlign;
           }
           for (int hb = h0; hb < h1; hb += d.merge)
@@ -444,7 +455,10 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     seg_start.push_back(row0);
     seg_len.push_back(rows);
     seg_v0.push_back(p->t_vpad);
-    for (int64_t r = 0; r < rows; ++r) p->row_vcol.push_back((int32_t)(p->t_vpad + vt_col_in_segment(r)));
+    for (int64_t r = 0; r < rows; ++r) {
+      p->row_vcol.push_back((int32_t)(p->t_vpad + vt_col_in_segment(r)));
+      p->row_seg.push_back((int32_t)(seg_start.size() - 1));
+    }
     p->t_vpad += (rows + kVtAlign - 1) / kVtAlign * kVtAlign;
     p->items.push_back(di);
     p->cu.push_back(row0 + rows);
@@ -455,6 +469,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads, seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
+  p->n_windows = (int)win_start.size();
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
   for (int c = 0; c < 3; ++c)
@@ -478,6 +493,8 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->off_vcol_win = place(off, p->row_vcol_win);
   p->off_work_win = place(off, p->work_win);
   p->off_rope = place(off, p->rope);
+  p->off_row_seg = place(off, p->row_seg);
+  p->off_row_seg_win = place(off, p->row_seg_win);
   p->meta_bytes = off;
   *out = p;
   return TCMV_OK;
@@ -610,6 +627,8 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
         g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->ldvt();
         g.vcol = dev<int32_t>(p, windowed ? p->off_vcol_win : p->off_vcol);
         if (d.pos == TCMV_POS_ROTARY_2D) { g.rope = dev<float>(p, p->off_rope); g.rope_dh = dh; }
+        // the queries leave the projection already multiplied by softmax scale * log2(e)
+        g.qcols = d.d; g.qscale = (float)(1.4426950408889634 / std::sqrt((double)dh));
       }
       else { g.ldc = 3 * d.d; }
       TCMV_CHECK(timed(ctx, TCMV_K_QKV_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "QKV GEMM");
@@ -623,7 +642,16 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       if (bf) {
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
         a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->ldvt();
-        a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
+        a.scale = 1.0f; a.prescaled = 1;
+        // largest key norm per (segment, head): lets the attention kernel drop the running maximum where
+        // the scores are provably small
+        uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
+        TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
+        TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
+                     return launch_knorm(qk + d.d, 2 * d.d, T, d.heads, dh,
+                                         dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
+                   "key norms");
+        a.kmax2 = kmax;
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
       } else {
         const float* q3 = reinterpret_cast<const float*>(qkv);
@@ -731,9 +759,9 @@ int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, cons
 }
 
 namespace {
-struct OpAttnLayout { size_t vcol, work, vt, total; int64_t t_vpad; int64_t T; int bq; };
+struct OpAttnLayout { size_t vcol, work, vt, rseg, kmax, kmax_bytes, total; int64_t t_vpad; int64_t T; int bq; };
 OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int heads, std::vector<int32_t>* vcol,
-                            std::vector<AttnWork>* work) {
+                            std::vector<AttnWork>* work, std::vector<int32_t>* rseg = nullptr) {
   OpAttnLayout L{};
   std::vector<int64_t> ss, sl, sv;
   int64_t vp = 0;
@@ -753,11 +781,19 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
     for (size_t s = 0; s < ss.size(); ++s)
       for (int64_t r = 0; r < sl[s]; ++r) (*vcol)[(size_t)(ss[s] + r)] = (int32_t)(sv[s] + vt_col_in_segment(r));
   }
+  if (rseg) {
+    rseg->assign((size_t)L.T, 0);
+    for (size_t s = 0; s < ss.size(); ++s)
+      for (int64_t r = 0; r < sl[s]; ++r) (*rseg)[(size_t)(ss[s] + r)] = (int32_t)s;
+  }
   size_t off = 0;
   L.vcol = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
   L.work = off; off = align_up(off + std::max<size_t>(wtmp.size() * sizeof(AttnWork), 16), 256);
   L.vt = off;
   if (dtype == TCMV_BF16) off = align_up(off + (size_t)d * vp * 2, 256);
+  L.rseg = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
+  L.kmax_bytes = align_up(std::max<size_t>(ss.size() * (size_t)heads * 4, 16), 256);
+  L.kmax = off; off += L.kmax_bytes;
   L.total = off;
   if (work) work->swap(wtmp);
   return L;
@@ -782,9 +818,9 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
     return TCMV_E_INVALID_ARG;
   const int dh = d / heads;
   if (dtype == TCMV_BF16 ? !(dh == 32 || dh == 64 || dh == 80 || dh == 96) : (dh % 16 || dh > 128)) return TCMV_E_UNSUPPORTED;
-  std::vector<int32_t> vcol;
+  std::vector<int32_t> vcol, rseg;
   std::vector<AttnWork> work;
-  const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work);
+  const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work, &rseg);
   if (L.T == 0) return TCMV_OK;
   if (!d_qkv || !d_out || !d_workspace) return TCMV_E_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return TCMV_E_INVALID_ARG;
@@ -794,6 +830,7 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
   // index data: blocking copies (this entry point is for checking and timing one kernel)
   if (hipMemcpy(wsb + L.vcol, vcol.data(), vcol.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
   if (hipMemcpy(wsb + L.work, work.data(), work.size() * sizeof(AttnWork), hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
+  if (hipMemcpy(wsb + L.rseg, rseg.data(), rseg.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
   AttnArgs a{};
   a.work = reinterpret_cast<const AttnWork*>(wsb + L.work); a.n_work = (int)work.size();
   a.heads = heads; a.dh = dh; a.t_total = L.T; a.out = d_out; a.ldo = d;
@@ -807,6 +844,13 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
     if (e != hipSuccess) return TCMV_E_HIP;
     a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = wsb + L.vt; a.ldv = L.t_vpad;
     a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
+    a.prescaled = 0;                               // the caller's queries are unscaled
+    uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + L.kmax);
+    e = launch_fill_zero(kmax, L.kmax_bytes, s);
+    if (e != hipSuccess) return TCMV_E_HIP;
+    e = launch_knorm(q + d, 3 * d, L.T, heads, dh, reinterpret_cast<const int32_t*>(wsb + L.rseg), kmax, s);
+    if (e != hipSuccess) return TCMV_E_HIP;
+    a.kmax2 = kmax;
     e = launch_attn_bf16(a, s);
   } else {
     const float* q = reinterpret_cast<const float*>(d_qkv);

@@ -70,7 +70,13 @@ struct AttnCfg {
 // global load.  Chunks are XOR-swizzled by (row/2)%8: the LDS serves 16 lanes x 16
 // bytes per clock over 64 banks and two 128-byte rows span the banks, so 16
 // consecutive rows reading the same logical chunk land on 16 different bank groups.
-template <int DH, int NT, int NWV = 4>
+// PRESC: the queries already carry the factor softmax scale * log2(e) (the QKV projection
+// applies it before rounding to bf16), so a score is directly the exponent of 2.
+// FAST: the kernel exists twice.  Both copies evaluate the same bound per workgroup (see below);
+// the FAST copy processes the workgroups whose scores are provably small without any softmax
+// reference and returns at once for the others, the other copy does the opposite.  Two
+// kernels instead of one branch keep the register allocation of each loop to itself.
+template <int DH, int NT, int NWV, bool PRESC, bool FAST>
 __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a) {
   using C = AttnCfg<DH>;
   constexpr int NTHREADS = NWV * 64;
@@ -112,6 +118,29 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     const uint16_t* qp = Q + (size_t)(w.q0 + qi) * a.ldqk + head * DH + lg * 8;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) qf[nt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+  // Does this workgroup need a running maximum at all?  |score| <= |q| * |k| (Cauchy-Schwarz);
+  // with the largest key norm of the segment (computed by knorm_kernel) every exponent of its
+  // queries is bounded.  If the bound is at most kSafeExp, 2^score cannot overflow or vanish in
+  // fp32 / bf16, the softmax needs no reference at all (it is shift invariant), and the
+  // per-element maximum, subtraction and rescaling are dropped.
+  constexpr float kSafeExp = 64.0f;
+  {
+    const float kmax2 = __uint_as_float(a.kmax2[(size_t)w.seg * a.heads + head]);
+    const float c2 = PRESC ? 1.0f : a.scale * a.scale;
+    bool ok = true;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      float q2 = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float v = (float)qf[nt][ks][e]; q2 = fmaf(v, v, q2); }
+      q2 += __shfl_xor(q2, 32, 64);                       // the two half-waves hold the two halves of a row
+      ok = ok && (q2 * kmax2 * c2 <= kSafeExp * kSafeExp);
+    }
+    const bool fast = __syncthreads_and(ok) != 0;
+    if (fast != FAST) return;
   }
 
   // Tile staging: global -> LDS directly (no registers, no LDS store instructions).  One
@@ -313,6 +342,69 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     return need;
   };
 
+  // The same region without a softmax reference (see `fast` above): probabilities are
+  // 2^score, nothing is tracked and nothing is ever rescaled.
+  auto region_fast = [&](auto masked, f32x16 (&s_next)[NT], const f32x16 (&s_cur)[NT], const uint8_t* sv_cur, int kb_cur,
+                         const uint8_t* sk_pref, int kb_pref, bool next_mask, int next_key0) {
+    float psum[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) psum[nt] = 0.f;
+    auto exp_half = [&](int j, bf16x8 (&pf)[NT]) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        uint32_t pk[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x0 = s_cur[nt][8 * j + 2 * e], x1 = s_cur[nt][8 * j + 2 * e + 1];
+          const float a0 = __builtin_amdgcn_exp2f(PRESC ? x0 : x0 * cs);
+          const float a1 = __builtin_amdgcn_exp2f(PRESC ? x1 : x1 * cs);
+          if (!C::ONES) psum[nt] += a0 + a1;
+          pk[e] = pack_bf16x2(a0, a1);
+        }
+        const uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        pf[nt] = __builtin_bit_cast(bf16x8, u);
+      }
+    };
+    auto v_frags = [&](int j, bf16x8 (&vf)[C::MT]) {
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        const int row = mt * 32 + lr;
+        vf[mt] = *reinterpret_cast<const bf16x8*>(sv_cur + row * (BKV * 2) + (((2 * (2 * kb_cur + j) + lg) ^ ((row >> 1) & 7)) << 4));
+      }
+    };
+    auto pv = [&](const bf16x8 (&vf)[C::MT], const bf16x8 (&pf)[NT]) {
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt], pf[nt], o[mt][nt], 0, 0, 0);
+    };
+    bf16x8 pf0[NT], pf1[NT], vf0[C::MT], vf1[C::MT];
+    score_block(s_next);
+    exp_half(0, pf0);
+    v_frags(0, vf0);
+    exp_half(1, pf1);
+    pv(vf0, pf0);
+    v_frags(1, vf1);
+    pv(vf1, pf1);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      if (!C::ONES) l_run[nt] += psum[nt];
+    k_frags(sk_pref, kb_pref);
+    if constexpr (decltype(masked)::value) {
+      if (next_mask) mask_block(s_next, next_key0);
+      __builtin_amdgcn_iglp_opt(3);
+    } else {
+      constexpr int n_mfma = C::KS * NT + 2 * C::MT * NT;
+      constexpr int n_valu = 16 * NT * (PRESC ? 1 : 2) + 8 * NT + (C::ONES ? 0 : 16 * NT) + 12;   // exp2 (+ scale), pack, sums, addresses
+#pragma unroll
+      for (int i = 0; i < n_mfma; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x402, (n_valu + n_mfma - 1) / n_mfma, 0);
+      }
+    }
+  };
+
   // ---- pipeline ---------------------------------------------------------------------
   // LDS ring of three stages.  At the barrier that opens iteration t, tile t+1 has landed (its
   // loads were issued one iteration earlier) and every wave is done with tile t-1, so tile
@@ -331,7 +423,7 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     score_block(s0);
     k_frags(smem, 1);
     if (ragged && n_tiles == 1) mask_block(s0, 0);
-    (void)stats_block(s0, alpha);                 // O is still zero: nothing to rescale
+    if (!FAST) (void)stats_block(s0, alpha);      // O is still zero: nothing to rescale
   }
   int st = 0;                                     // stage of tile t
   // iteration t: block 0 of tile t (scores in s0) and block 1 (scored in the first region);
@@ -346,11 +438,16 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     wait_tile();
     __syncthreads();
     if (t + 2 < n_tiles) load_tile(t + 2, st2, ragged && (t + 3 == n_tiles));
-    float alpha[NT];
-    bool need = region(masked, s1, s0, sv, 0, sk1, 0, true, ragged && t + 1 == n_tiles, j0 + 32, alpha);
-    if (__builtin_expect(__any(need), 0)) rescale(alpha);
-    need = region(masked, s0, s1, sv, 1, sk1, 1, t + 1 < n_tiles, ragged && t + 2 == n_tiles, j0 + BKV, alpha);
-    if (__builtin_expect(__any(need), 0)) rescale(alpha);
+    if constexpr (FAST) {
+      region_fast(masked, s1, s0, sv, 0, sk1, 0, ragged && t + 1 == n_tiles, j0 + 32);
+      region_fast(masked, s0, s1, sv, 1, sk1, 1, ragged && t + 2 == n_tiles, j0 + BKV);
+    } else {
+      float alpha[NT];
+      bool need = region(masked, s1, s0, sv, 0, sk1, 0, true, ragged && t + 1 == n_tiles, j0 + 32, alpha);
+      if (__builtin_expect(__any(need), 0)) rescale(alpha);
+      need = region(masked, s0, s1, sv, 1, sk1, 1, t + 1 < n_tiles, ragged && t + 2 == n_tiles, j0 + BKV, alpha);
+      if (__builtin_expect(__any(need), 0)) rescale(alpha);
+    }
     st = st1;
   };
   // only the last two iterations can meet masked blocks (ragged tail) or the ignored extra block
@@ -388,28 +485,99 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   }
 }
 
-hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
-  if (a.n_work == 0 || a.heads == 0) return hipSuccess;
-  const int64_t total = (int64_t)a.n_work * a.heads;
-  if (total > (1 << 30)) return hipErrorInvalidValue;
-  if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
-  if (a.bq != 128 && a.bq != 256 && a.bq != 512) return hipErrorInvalidValue;
-  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-#define TCMV_ATTN_CASE(D)                                                                         \
-  case D:                                                                                         \
-    if (a.bq == 512) hipLaunchKernelGGL((attn_bf16_kernel<D, 2, 8>), dim3(grid), dim3(512), 0, s, a); \
-    else if (a.bq == 256) hipLaunchKernelGGL((attn_bf16_kernel<D, 2>), dim3(grid), dim3(kThreads4), 0, s, a); \
-    else hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), dim3(grid), dim3(kThreads4), 0, s, a);       \
+template <bool PRESC, bool FAST>
+static hipError_t launch_attn_t(const AttnArgs& a, unsigned grid, hipStream_t s) {
+#define TCMV_ATTN_CASE(D)                                                                                     \
+  case D:                                                                                                     \
+    if (a.bq == 512) hipLaunchKernelGGL((attn_bf16_kernel<D, 2, 8, PRESC, FAST>), dim3(grid), dim3(512), 0, s, a);  \
+    else if (a.bq == 256) hipLaunchKernelGGL((attn_bf16_kernel<D, 2, 4, PRESC, FAST>), dim3(grid), dim3(kThreads4), 0, s, a); \
+    else hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, PRESC, FAST>), dim3(grid), dim3(kThreads4), 0, s, a);  \
     break;
   switch (a.dh) {
     TCMV_ATTN_CASE(32) TCMV_ATTN_CASE(64) TCMV_ATTN_CASE(80)
     case 96:   // the register file holds one query tile per wave only
       if (a.bq != 128) return hipErrorInvalidValue;
-      hipLaunchKernelGGL((attn_bf16_kernel<96, 1>), dim3(grid), dim3(kThreads4), 0, s, a);
+      hipLaunchKernelGGL((attn_bf16_kernel<96, 1, 4, PRESC, FAST>), dim3(grid), dim3(kThreads4), 0, s, a);
       break;
     default: return hipErrorInvalidValue;
   }
 #undef TCMV_ATTN_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
+  if (a.n_work == 0 || a.heads == 0) return hipSuccess;
+  const int64_t total = (int64_t)a.n_work * a.heads;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4 || !a.kmax2) return hipErrorInvalidValue;
+  if (a.bq != 128 && a.bq != 256 && a.bq != 512) return hipErrorInvalidValue;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+  // both copies visit every work item; each item is processed by exactly one of them
+  hipError_t e = a.prescaled ? launch_attn_t<true, true>(a, grid, s) : launch_attn_t<false, true>(a, grid, s);
+  if (e != hipSuccess) return e;
+  return a.prescaled ? launch_attn_t<true, false>(a, grid, s) : launch_attn_t<false, false>(a, grid, s);
+}
+
+// Largest squared key norm per (segment, head), the input of the attention kernel's decision
+// whether a running maximum is needed.  A workgroup takes 32 rows: every thread squares and
+// sums 16-byte chunks (coalesced along the row), the chunks of a head are added up through
+// LDS, then one thread per head walks the 32 rows and issues one atomic max per run of rows
+// of the same segment (norms are >= 0, so their float bits order like unsigned integers).
+__global__ __launch_bounds__(256) void knorm_kernel(const uint16_t* k, int64_t ldk, int64_t rows, int heads, int cph,
+                                                    const int32_t* row_seg, uint32_t* kmax2) {
+  constexpr int R = 32;
+  extern __shared__ float part[];                    // [R][heads * cph] chunk sums, then [R][heads] norms
+  const int cpr = heads * cph;                       // 16-byte chunks per row
+  const int64_t r0 = (int64_t)blockIdx.x * R;
+  const int nr = (int)min((int64_t)R, rows - r0);
+  for (int i = threadIdx.x; i < nr * cpr; i += 256) {
+    const int r = i / cpr, c = i - r * cpr;
+    const uint4 u = *reinterpret_cast<const uint4*>(k + (r0 + r) * ldk + c * 8);
+    const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+    float sq = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float lo = __uint_as_float(wds[j] << 16), hi = __uint_as_float(wds[j] & 0xFFFF0000u);
+      sq = fmaf(lo, lo, sq);
+      sq = fmaf(hi, hi, sq);
+    }
+    part[i] = sq;
+  }
+  __syncthreads();
+  float* norm = part + R * cpr;
+  for (int i = threadIdx.x; i < nr * heads; i += 256) {
+    const int r = i / heads, h = i - r * heads;
+    float sq = 0.f;
+    for (int c = 0; c < cph; ++c) sq += part[r * cpr + h * cph + c];
+    norm[i] = sq;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < heads) {
+    const int h = threadIdx.x;
+    int seg = row_seg[r0];
+    float mx = 0.f;
+    for (int r = 0; r < nr; ++r) {
+      const int sg = row_seg[r0 + r];
+      if (sg != seg) {
+        atomicMax(kmax2 + (size_t)seg * heads + h, __float_as_uint(mx));
+        seg = sg;
+        mx = 0.f;
+      }
+      mx = fmaxf(mx, norm[r * heads + h]);
+    }
+    atomicMax(kmax2 + (size_t)seg * heads + h, __float_as_uint(mx));
+  }
+}
+
+hipError_t launch_knorm(const void* k, int64_t ldk, int64_t rows, int heads, int dh, const int32_t* row_seg,
+                        uint32_t* kmax2, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  if (dh % 8 || heads <= 0 || heads > 256 || ldk % 8) return hipErrorInvalidValue;
+  const int cph = dh / 8;
+  const size_t lds = (size_t)32 * heads * (cph + 1) * sizeof(float);
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(knorm_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), lds, s,
+                     reinterpret_cast<const uint16_t*>(k), ldk, rows, heads, cph, row_seg, kmax2);
   return hipGetLastError();
 }
 

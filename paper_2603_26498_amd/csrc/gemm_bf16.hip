@@ -227,6 +227,7 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
         *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + (col >> 1)) = pack_bf16x2(h0, h1);
       } else if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
         if (EPI == EPI_QKV && col >= g.split) continue;
+        if (EPI == EPI_QKV && col < g.qcols) { val.x *= g.qscale; val.y *= g.qscale; val.z *= g.qscale; val.w *= g.qscale; }
         if (EPI == EPI_QKV && g.rope) {
           // rotary positions: the lane holds element pairs p and p+1 of one head (col % 4 == 0, head size % 4 == 0)
           const int p2 = ((col % g.rope_dh) >> 1) * 2;

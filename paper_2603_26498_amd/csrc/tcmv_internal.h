@@ -28,7 +28,8 @@ struct AttnWork {
   int seg_start; // first row of the segment
   int seg_len;   // rows of the segment
   int v0;        // first column of the segment in the transposed-V buffer
-  int pad_[3];
+  int seg;       // index of the segment (row of the key-norm table)
+  int pad_[2];
 };
 
 enum Epilogue {
@@ -54,6 +55,8 @@ struct GemmArgs {
   // EPI_QKV with rotary positions: rope[row][p] = (cos, sin) of pair p of a head, p < rope_dh/2;
   // applied to the columns below split (q and k)
   const float* rope; int rope_dh;
+  // EPI_QKV: columns below qcols (the queries) are multiplied by qscale before rounding (0 columns = off)
+  int qcols; float qscale;
 };
 
 struct AttnArgs {
@@ -64,7 +67,9 @@ struct AttnArgs {
   int heads, dh;
   int bq;                                        // query rows per work item the list was built with (bf16: 128, 256 or 512)
   int64_t t_total;                               // rows of q/k (for clamping)
-  float scale;
+  float scale;                                   // softmax scale * log2(e); 1 when the queries already carry it
+  int prescaled;                                 // bf16 path: the queries already carry the scale
+  const uint32_t* kmax2;                         // bf16 path, may be null: [segments][heads] largest squared key norm (float bits)
 };
 
 struct PreprocArgs {
@@ -93,6 +98,10 @@ hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
 // vt[c][vcol[r]] = v[r][c] for r < rows, c < d  (bf16)
 hipError_t launch_transpose_v(const void* v, int64_t ldv, const int32_t* vcol, void* vt, int64_t ldvt,
                               int64_t rows, int d, hipStream_t s);
+// kmax2[row_seg[r]][h] = max(kmax2[..], |k[r, h*dh .. (h+1)*dh)|^2) over all rows (bf16 keys, row stride ldk elements);
+// kmax2 holds float bits and must be zero-filled before the call
+hipError_t launch_knorm(const void* k, int64_t ldk, int64_t rows, int heads, int dh, const int32_t* row_seg,
+                        uint32_t* kmax2, hipStream_t s);
 // zero fill of a 16-byte aligned region whose size is a multiple of 16
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 // hidden[cls_rows[i]] = cls + pos0[0] (if pos0)
