@@ -50,6 +50,7 @@ struct tcmv_plan {
   int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
   int n_segments = 0;
   int bq = 0;                         // query rows per attention work item of the full-segment layers
+  bool norm_bound = false, norm_bound_win = false;   // worth computing key norms (long segments / long windows)
   // device copy (allocated on first device use)
   uint8_t* d_meta = nullptr;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
@@ -469,6 +470,15 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads, seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
+  // The key-norm pass costs one read of K per layer; what it can save grows with the number of keys per query.
+  // It pays from about 2048 keys per query on average.
+  auto long_enough = [](const std::vector<int64_t>& len) {
+    double rows = 0, pairs = 0;
+    for (int64_t n : len) { rows += (double)n; pairs += (double)n * (double)n; }
+    return rows > 0 && pairs >= 2048.0 * rows;
+  };
+  p->norm_bound = d.dtype == TCMV_BF16 && long_enough(seg_len);
+  p->norm_bound_win = d.dtype == TCMV_BF16 && long_enough(win_len);
   p->n_windows = (int)win_start.size();
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
@@ -645,13 +655,15 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
         a.scale = 1.0f; a.prescaled = 1;
         // largest key norm per (segment, head): lets the attention kernel drop the running maximum where
         // the scores are provably small
-        uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
-        TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
-        TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
-                     return launch_knorm(qk + d.d, 2 * d.d, T, d.heads, dh,
-                                         dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
-                   "key norms");
-        a.kmax2 = kmax;
+        if (windowed ? p->norm_bound_win : p->norm_bound) {
+          uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
+          TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
+          TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
+                       return launch_knorm(qk + d.d, 2 * d.d, T, d.heads, dh,
+                                           dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
+                     "key norms");
+          a.kmax2 = kmax;
+        }
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
       } else {
         const float* q3 = reinterpret_cast<const float*>(qkv);

@@ -125,7 +125,9 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   // fp32 / bf16, the softmax needs no reference at all (it is shift invariant), and the
   // per-element maximum, subtraction and rescaling are dropped.
   constexpr float kSafeExp = 64.0f;
-  {
+  if (!a.kmax2) {            // no key norms: the caller wants every workgroup to take the reference-tracking copy
+    if (FAST) return;
+  } else {
     const float kmax2 = __uint_as_float(a.kmax2[(size_t)w.seg * a.heads + head]);
     const float c2 = PRESC ? 1.0f : a.scale * a.scale;
     bool ok = true;
@@ -509,12 +511,15 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work == 0 || a.heads == 0) return hipSuccess;
   const int64_t total = (int64_t)a.n_work * a.heads;
   if (total > (1 << 30)) return hipErrorInvalidValue;
-  if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4 || !a.kmax2) return hipErrorInvalidValue;
+  if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
   if (a.bq != 128 && a.bq != 256 && a.bq != 512) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-  // both copies visit every work item; each item is processed by exactly one of them
-  hipError_t e = a.prescaled ? launch_attn_t<true, true>(a, grid, s) : launch_attn_t<false, true>(a, grid, s);
-  if (e != hipSuccess) return e;
+  // with key norms both copies visit every work item and each item is processed by exactly one of them;
+  // without, only the reference-tracking copy runs
+  if (a.kmax2) {
+    const hipError_t e = a.prescaled ? launch_attn_t<true, true>(a, grid, s) : launch_attn_t<false, true>(a, grid, s);
+    if (e != hipSuccess) return e;
+  }
   return a.prescaled ? launch_attn_t<true, false>(a, grid, s) : launch_attn_t<false, false>(a, grid, s);
 }
 

@@ -174,3 +174,19 @@ def test_per_request_pipeline_matches_plan_by_plan_runs():
             assert_tokens_close(out[r0:r0 + a.shape[0]], a, 2e-2, 0.999, f"{wl.name} request rows")
             r0 += a.shape[0]
         assert r0 == out.shape[0]
+
+
+@pytest.mark.parametrize("std", [0.02, 0.08])
+def test_long_segments_take_the_norm_bounded_attention_path(std):
+    """Segments of 4096 and 2304 tokens make the library compute key norms and run attention without a softmax
+    reference where the bound allows it; the result must not depend on which copy of the kernel ran."""
+    desc = workloads.qwen_like_desc(layers=2, d=320, heads=4, mlp=640, out_dim=192, max_grid=48)
+    rng = np.random.default_rng(9)
+    items = [workloads.Item(2, 8, 448, 448, 448, 448, workloads.random_frames(rng, 8, 448, 448)),
+             workloads.Item(1, 1, 672, 672, 672, 672, workloads.random_frames(rng, 1, 672, 672))]
+    wl = workloads.Workload("long", desc, items, workloads.make_weights(desc, 31, std=std, random_affine=True))
+    ref = oracle.run(wl, workers=4)
+    enc, pl, patches, hidden, out = run_gpu(wl)
+    assert pl.cu_seqlens == [0, 4096, 4096 + 2304]
+    assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], 2e-2, 0.999, "long segments hidden")
+    assert_tokens_close(out.float().cpu().numpy(), ref["out"], 2e-2, 0.999, "long segments out")
