@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_attention_hbm_traffic.txt).
 # Valid only for the kernel source it was taken with: reported as null once that file changes.
-ATTN_TRAFFIC = {"source_sha256": "5d60d31d61e302b4456c5740d969b675b4f8ef83f2ff278c1d5627929c90b553",
+ATTN_TRAFFIC = {"source_sha256": "8cdb484e3e83c8a59bbc250ebed95098728d63f8245f77dc2d0e7a59cfa1e3a4",
                 "workload": "cfg4_video64x448_vit32x1280_proj3584",
-                "fetch_bytes": 557357 * 1024, "write_bytes": 81939 * 1024}
+                "fetch_bytes": 639557 * 1024, "write_bytes": 82436 * 1024}
 
 
 def measured_traffic(kernel, workload):

@@ -151,7 +151,8 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   }
   w.h = off; off = align_up(off + T * d.mlp * e, 256);   // gated MLP: the product silu(gate)*up, also [T, mlp]
   // largest squared key norm per (segment or window, head)
-  w.kmax_bytes = align_up((size_t)std::max(p->n_segments, p->n_windows) * d.heads * 4, 256);
+  // (+ one word behind the table: "some workgroup needs the reference-tracking kernel")
+  w.kmax_bytes = align_up(((size_t)std::max(p->n_segments, p->n_windows) * d.heads + 1) * 4, 256);
   w.kmax = off; off += d.dtype == TCMV_BF16 ? w.kmax_bytes : 0;
   w.total = off;
   return w;
@@ -663,6 +664,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
                                            dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
                      "key norms");
           a.kmax2 = kmax;
+          a.any_left = kmax + (size_t)std::max(p->n_segments, p->n_windows) * d.heads;
         }
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
       } else {
@@ -771,7 +773,7 @@ int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, cons
 }
 
 namespace {
-struct OpAttnLayout { size_t vcol, work, vt, rseg, kmax, kmax_bytes, total; int64_t t_vpad; int64_t T; int bq; };
+struct OpAttnLayout { size_t vcol, work, vt, rseg, kmax, kmax_bytes, total; int64_t t_vpad; int64_t T; int bq; size_t n_seg; };
 OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int heads, std::vector<int32_t>* vcol,
                             std::vector<AttnWork>* work, std::vector<int32_t>* rseg = nullptr) {
   OpAttnLayout L{};
@@ -804,8 +806,9 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   L.vt = off;
   if (dtype == TCMV_BF16) off = align_up(off + (size_t)d * vp * 2, 256);
   L.rseg = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
-  L.kmax_bytes = align_up(std::max<size_t>(ss.size() * (size_t)heads * 4, 16), 256);
+  L.kmax_bytes = align_up((ss.size() * (size_t)heads + 1) * 4, 256);
   L.kmax = off; off += L.kmax_bytes;
+  L.n_seg = ss.size();
   L.total = off;
   if (work) work->swap(wtmp);
   return L;
@@ -863,6 +866,7 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
     e = launch_knorm(q + d, 3 * d, L.T, heads, dh, reinterpret_cast<const int32_t*>(wsb + L.rseg), kmax, s);
     if (e != hipSuccess) return TCMV_E_HIP;
     a.kmax2 = kmax;
+    a.any_left = kmax + L.n_seg * (size_t)heads;
     e = launch_attn_bf16(a, s);
   } else {
     const float* q = reinterpret_cast<const float*>(d_qkv);

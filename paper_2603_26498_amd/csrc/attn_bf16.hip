@@ -91,6 +91,9 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   const int head = p / a.n_work;
   const AttnWork w = a.work[p - head * a.n_work];
 
+  // the reference-tracking copy runs after the other one (same stream), which has recorded whether it
+  // left any workgroup behind
+  if (!FAST && a.kmax2 && a.any_left && *a.any_left == 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __builtin_assume(tid >= 0 && tid < NTHREADS);
   const int lr = lane & 31, lg = lane >> 5;
@@ -142,6 +145,7 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
       ok = ok && (q2 * kmax2 * c2 <= kSafeExp * kSafeExp);
     }
     const bool fast = __syncthreads_and(ok) != 0;
+    if (FAST && !fast && a.any_left && tid == 0) atomicOr(a.any_left, 1u);
     if (fast != FAST) return;
   }
 

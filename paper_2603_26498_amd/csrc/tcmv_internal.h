@@ -70,6 +70,7 @@ struct AttnArgs {
   float scale;                                   // softmax scale * log2(e); 1 when the queries already carry it
   int prescaled;                                 // bf16 path: the queries already carry the scale
   const uint32_t* kmax2;                         // bf16 path, may be null: [segments][heads] largest squared key norm (float bits)
+  uint32_t* any_left;                            // with kmax2, may be null: zeroed word; set when a workgroup needs the reference-tracking copy
 };
 
 struct PreprocArgs {
