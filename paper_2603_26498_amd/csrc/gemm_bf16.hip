@@ -135,25 +135,30 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
     }
     const uint8_t* sa = smem + buf * STAGE;
     const uint8_t* sb = sa + A_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MI], bfr[NI];
+    // fragments double-buffered in registers: the LDS reads of k-step kk+1 are issued before the MFMAs of kk
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto frags = [&](int kk, int b) {
       const int ch = kk * 2 + lg;
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
         const int row = wm * TM + mi * 32 + lr;
-        af[mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
+        af[b][mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
       }
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
         const int row = wn * TN + ni * 32 + lr;
-        bfr[ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
+        bfr[b][ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
       }
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) frags(kk + 1, (kk + 1) & 1);
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][ni], af[kk & 1][mi], acc[mi][ni], 0, 0, 0);
     }
     if (++buf == NSTAGE) buf = 0;
   }
