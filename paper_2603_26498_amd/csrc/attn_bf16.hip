@@ -1,6 +1,11 @@
 // Bidirectional block-diagonal attention on bf16 MFMA (gfx950), flash style:
-// scores are never written to memory; softmax statistics are kept per query in
-// fp32 and updated block by block (online softmax).
+// scores are never written to memory.  Two copies of one kernel: the general one
+// keeps softmax statistics per query in fp32 and updates them block by block
+// (online softmax); the other one handles the workgroups whose scores are
+// provably small (from key and query norms) and exponentiates them directly,
+// with no running maximum at all.  On this hardware the kernel is limited by the
+// vector issue port (every MFMA also takes about 12 of its cycles, every exp2
+// 16), so vector instructions per score are what counts.
 //
 // Work decomposition: one workgroup (NWV = 4 or 8 waves) = 32*NT*NWV query rows of
 // one segment and one head; each wave owns NT tiles of 32 query rows.  Eight
@@ -9,8 +14,7 @@
 // tiles of 64 keys are staged in LDS by direct global->LDS loads (a ring of
 // three stages, the loads of tile t+2 are in flight while tile t is consumed)
 // and shared by the waves of the workgroup.  Every K / V^T
-// fragment read from LDS feeds NT MFMAs: LDS bandwidth (about 128 B/clk/CU) is
-// the first limit of this kernel, and NT = 2 halves the LDS bytes per FLOP.
+// fragment read from LDS feeds NT MFMAs: NT = 2 halves the LDS bytes per FLOP.
 //
 // The kernel computes S^T = K * Q^T (keys are the MFMA row dimension).  In the
 // 32x32 accumulator layout a lane then holds ONE query column and 16 keys, so
@@ -58,7 +62,6 @@ struct AttnCfg {
   static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int KROWCH = KCH | 1;                   // chunks per K row in LDS incl. padding
   static constexpr int NW = KROWCH + DH / 8;               // wave-wide 1 KB loads per tile (K rows, then V^T rows)
-  static constexpr int NI = (NW + 3) / 4;                  // loads per wave (4 waves)
 };
 
 // V^T tile in LDS: row = head-dim index (128 bytes = 64 keys).  Inside a row the
