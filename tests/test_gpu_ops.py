@@ -252,3 +252,30 @@ def test_gated_epilogue(m, n2, k):
     got = c.float().cpu().numpy()
     assert np.abs(got - ref).max() <= 2 ** -7 * np.abs(ref).max()
     assert_tokens_close(got, ref, 1e-2, 0.9999, "gated epilogue")
+
+
+def test_attention_mixed_norm_bounds_in_one_launch():
+    """Some (segment, head, query tile) combinations have provably small scores and are exponentiated without
+    a softmax reference, others in the same launch are not: head 0 has large queries, one block of query rows
+    of head 1 is large, one segment has large keys.  Every row must come out right whichever copy handled it."""
+    rng = np.random.default_rng(123)
+    d, heads, dh = 240, 3, 80
+    lens = [700, 1300, 520]
+    cu = [0] + list(np.cumsum(lens))
+    T = cu[-1]
+    q = rng.normal(0, 1.0, (T, d)); k = rng.normal(0, 1.0, (T, d)); v = rng.normal(0, 1.0, (T, d))
+    q[:, :dh] *= 7.0                       # head 0: bound far above the limit everywhere
+    q[300:556, dh:2 * dh] *= 7.0           # head 1: one tile of queries in segment 0
+    k[cu[2]:, 2 * dh:] *= 6.0              # head 2: large keys in the last segment only
+    qkv = bf16_grid(np.concatenate([q, k, v], 1).astype(np.float32))
+    x = qkv.astype(np.float64)
+    ref = oe.attention(x[:, :d], x[:, d:2 * d], x[:, 2 * d:], cu, heads)
+    got = _attn("bf16", qkv, [int(c) for c in cu], d, heads)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= 1.2e-2 * np.abs(ref).max()
+    assert_tokens_close(got, ref, 2e-2, 0.9995, "attention, mixed bounds")
+    # the same rows, recomputed with uniformly small inputs elsewhere, do not change (no interaction between copies)
+    small = qkv.copy()
+    small[:, :dh] = qkv[:, :dh] / 7.0
+    got2 = _attn("bf16", bf16_grid(small), [int(c) for c in cu], d, heads)
+    assert np.array_equal(got[:, dh:], got2[:, dh:])
