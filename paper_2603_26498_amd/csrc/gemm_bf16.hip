@@ -21,6 +21,7 @@
 // Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each walk
 // a contiguous range of tiles: neighbouring tiles share A rows or W rows in the
 // XCD's own L2.
+#include <type_traits>
 #include "tcmv_internal.h"
 #include "device_utils.h"
 
@@ -171,51 +172,34 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
   // residual read-modify-write are full contiguous segments.  Only the transposed-V
   // part of the QKV projection keeps the register layout (there consecutive lanes =
   // consecutive tokens is exactly the contiguous direction).
-  constexpr int EPS = TN + 4;                      // padded row stride of the staging buffer (floats)
+  // A wave tile whose width divides 256 columns goes through the buffer in one piece; any
+  // other width (160 columns of the 256x320 tile) in groups of two 32-column tiles, the odd
+  // one last.
+  constexpr int GN = (256 % TN == 0) ? NI : 2;     // 32-column tiles per group
+  constexpr int EPS = GN * 32 + 4;                 // padded row stride of the staging buffer (floats)
   static_assert(WAVES * 32 * EPS * 4 <= NSTAGE * STAGE, "epilogue staging does not fit in the operand stages");
-  static_assert(256 % TN == 0 && TN % 4 == 0, "wave tile width");
-  constexpr int LPR = TN / 4;                      // lanes per row when reading back
-  constexpr int RPP = 64 / LPR;                    // rows per read pass
+  static_assert(TN % 32 == 0, "wave tile width");
   __syncthreads();                                 // every wave is done with the operand stages
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPS);
   const int wcol0 = n0 + wn * TN;
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int64_t rbase = m0 + wm * TM + mi * 32;
-    if (EPI == EPI_QKV && wcol0 + TN > g.split) {
-      // transposed-V columns straight from registers
-      const int64_t row = rbase + lr;
-      if (row < g.m) {
-        const int vc = g.vcol[row];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-          for (int vq = 0; vq < 4; ++vq) {
-            const int col = wcol0 + ni * 32 + 8 * vq + 4 * lg;
-            if (col >= g.split && col < g.n) {
-              float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-              if (g.bias) b4 = *reinterpret_cast<const float4*>(g.bias + col);
-              uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
-              vt[0] = f32_to_bf16(acc[mi][ni][4 * vq] + b4.x);
-              vt[g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 1] + b4.y);
-              vt[2 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 2] + b4.z);
-              vt[3 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 3] + b4.w);
-            }
-          }
-      }
-      if (wcol0 >= g.split) continue;              // nothing else in this wave tile
-    }
+
+  // one group of NGT tiles (columns nb*32 .. nb*32 + NGT*32 of the wave tile) of 32 rows: registers -> LDS -> global
+  auto flush = [&](auto ngc, int mi, int nb, int64_t rbase) {
+    constexpr int NGT = decltype(ngc)::value;
+    constexpr int LPR = NGT * 8;                   // lanes per row when reading back
+    constexpr int RPP = 64 / LPR;                  // rows per read pass
     // registers -> LDS (lane = row)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+    for (int ni = 0; ni < NGT; ++ni)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq)
         *reinterpret_cast<float4*>(ep + lr * EPS + ni * 32 + 8 * vq + 4 * lg) =
-            make_float4(acc[mi][ni][4 * vq], acc[mi][ni][4 * vq + 1], acc[mi][ni][4 * vq + 2], acc[mi][ni][4 * vq + 3]);
+            make_float4(acc[mi][nb + ni][4 * vq], acc[mi][nb + ni][4 * vq + 1], acc[mi][nb + ni][4 * vq + 2],
+                        acc[mi][nb + ni][4 * vq + 3]);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same-wave LDS ops complete in order; keep the compiler from reordering
     // LDS -> global (lanes along the row)
     const int c4 = (lane % LPR) * 4;
-    const int col = wcol0 + c4;
+    const int col = wcol0 + nb * 32 + c4;
     float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (g.bias && col < g.n) b4 = *reinterpret_cast<const float4*>(g.bias + col);
 #pragma unroll
@@ -267,7 +251,40 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col) = val;
       }
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next block overwrites the buffer
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next group overwrites the buffer
+  };
+
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int64_t rbase = m0 + wm * TM + mi * 32;
+    if (EPI == EPI_QKV && wcol0 + TN > g.split) {
+      // transposed-V columns straight from registers
+      const int64_t row = rbase + lr;
+      if (row < g.m) {
+        const int vc = g.vcol[row];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int col = wcol0 + ni * 32 + 8 * vq + 4 * lg;
+            if (col >= g.split && col < g.n) {
+              float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+              if (g.bias) b4 = *reinterpret_cast<const float4*>(g.bias + col);
+              uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
+              vt[0] = f32_to_bf16(acc[mi][ni][4 * vq] + b4.x);
+              vt[g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 1] + b4.y);
+              vt[2 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 2] + b4.z);
+              vt[3 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 3] + b4.w);
+            }
+          }
+      }
+      if (wcol0 >= g.split) continue;              // nothing else in this wave tile
+    }
+#pragma unroll
+    for (int nb = 0; nb < NI; nb += GN) {
+      if (nb + GN <= NI) flush(std::integral_constant<int, GN>{}, mi, nb, rbase);
+      else flush(std::integral_constant<int, 1>{}, mi, nb, rbase);
+    }
   }
 }
 
@@ -314,7 +331,17 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // shape; 128x128 tiles (4 waves, two workgroups per CU) otherwise.  (Measured on the
   // encoder's shapes.)
   const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
-  if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560 || big_tiles >= 1024)) return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+  if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560 || big_tiles >= 1024)) {
+    // one workgroup per CU and 256 CUs: the launch takes ceil(tiles / 256) rounds of one tile
+    // time each.  A tile 320 columns wide is taken where it saves rounds' worth of tile area
+    // (hidden sizes that are multiples of 320 but not of 256, such as 1280).
+    auto area = [&](int64_t bm, int64_t bn) {
+      const int64_t t = ((a.m + bm - 1) / bm) * ((a.n + bn - 1) / bn);
+      return ((t + 255) / 256) * bm * bn;
+    };
+    if (area(256, 320) * 100 < area(256, 256) * 97) return launch_cfg<256, 320, 4, 2, 64, 2, 1>(a, s);
+    return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+  }
   // a single small request: fewer than 200 tiles of 128x128 leave most CUs idle; 64x64 tiles
   // (2 waves) quadruple the number of workgroups
   const int64_t mid_tiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);

@@ -221,6 +221,32 @@ def test_gemm_bf16_large_tile_path_with_ragged_rows():
         assert np.abs(got - ref).max() <= tol, epi
 
 
+def test_gemm_bf16_wide_tile_path_with_ragged_rows_and_columns():
+    """A shape for which tiles 320 columns wide need fewer rounds over the CUs than 256x256 ones (640 -> 512
+    tiles on 256 CUs): the wave tiles are 160 columns wide and leave the kernel in column groups of 64, 64
+    and 32.  Last row tile and last column tile ragged; the gated epilogue goes the same way."""
+    rng = np.random.default_rng(78)
+    m, n, k = 8100, 5112, 128
+    a = bf16_grid(rng.normal(0, 1, (m, k)))
+    w = bf16_grid(rng.normal(0, 0.05, (n, k)))
+    bias = rng.normal(0, 0.5, n).astype(np.float32)
+    for epi in (B.EPI_STORE, B.EPI_GELU, B.EPI_RESID):
+        c0 = rng.normal(0, 1, (m, n)).astype(np.float32)
+        ref = _gemm_ref(a, w, bias, epi, c0)
+        c = dev(c0) if epi == B.EPI_RESID else torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+        B.tcmv_op_gemm(B.TCMV_BF16, epi, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+        sync()
+        got = c.float().cpu().numpy()
+        tol = 1e-4 * max(1.0, np.abs(ref).max()) if epi == B.EPI_RESID else 2 ** -8 * np.abs(ref).max() + 1e-5
+        assert np.abs(got - ref).max() <= tol, epi
+    u = a.astype(np.float64) @ w.astype(np.float64).T + bias
+    ref = oe.silu(u[:, 0::2]) * u[:, 1::2]
+    c = torch.full((m, n // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.tcmv_op_gemm(B.TCMV_BF16, B.EPI_GATED, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+    sync()
+    assert np.abs(c.float().cpu().numpy() - ref).max() <= 2 ** -7 * np.abs(ref).max()
+
+
 # ---------------------------------------------------------------- encoder-family variants
 @pytest.mark.parametrize("rows,d", [(3, 320), (1030, 1280), (77, 64)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
