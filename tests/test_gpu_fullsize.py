@@ -40,7 +40,7 @@ def _sample(cu, n, seed):
     return np.array(sorted(pick), np.int64)
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 8])
 def test_full_preprocess_bit_exact(idx):
     wl = workloads.full_config(idx, with_weights=False, layers=0)
     wl.weights = workloads.make_weights(wl.desc, 1)
@@ -61,7 +61,7 @@ def test_full_preprocess_bit_exact(idx):
     assert row == pl.info.n_patch_rows
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70, 8])
 def test_full_token_count_one_layer_sampled_rows(idx):
     if idx == 70:                      # the windowed family's full-attention layer (rotary positions, 32768 keys)
         idx = 7
@@ -94,7 +94,7 @@ def test_full_token_count_one_layer_sampled_rows(idx):
     assert rel.max() <= 8e-3, rel.max()
 
 
-@pytest.mark.parametrize("idx", [3, 4])
+@pytest.mark.parametrize("idx", [3, 4, 8])
 def test_full_size_projector_sampled_rows(idx):
     wl = workloads.full_config(idx, with_frames=False, layers=0)
     desc, w = wl.desc, wl.weights
@@ -106,14 +106,15 @@ def test_full_size_projector_sampled_rows(idx):
     out = enc.merge_project(pl, hidden.to("cuda:0"))
     torch.cuda.synchronize()
     rng = np.random.default_rng(idx)
-    groups = np.unique(np.concatenate([[0, T // 4 - 1], rng.integers(0, T // 4, 126)]))
-    rows = (groups[:, None] * 4 + np.arange(4)[None, :]).reshape(-1)
+    m2 = desc.merge ** 2
+    groups = np.unique(np.concatenate([[0, T // m2 - 1], rng.integers(0, T // m2, 126)]))
+    rows = (groups[:, None] * m2 + np.arange(m2)[None, :]).reshape(-1)
     ref = oe.merge_project(hidden.numpy()[rows].astype(np.float64), desc, w)
     got = out[torch.from_numpy(groups).to(out.device)].float().cpu().numpy()
     assert_tokens_close(got, ref, 2e-2, 0.999, f"cfg{idx} projector")
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_full_depth_against_stored_reference_rows(idx):
     path = os.path.join(GOLD, f"full_cfg{idx}.npz")
     if not os.path.exists(path):

@@ -266,8 +266,26 @@ def config7(n_frames=64, side=448, layers=32, with_frames=True, desc=None) -> Wo
     return wl
 
 
+def plain_rotary_desc(layers=24, d=1024, heads=16, mlp=4096, out_dim=5120) -> ModelDesc:
+    """The third encoder family of Table 1: images of any size cut into 16x16 patches, no
+    temporal patch and no spatial merge, rotary 2-D positions, RMSNorm, gated MLP, full
+    attention in every layer; a two-layer adapter maps every token to the LLM width."""
+    return ModelDesc(dtype="bf16", layers=layers, d=d, heads=heads, mlp=mlp, patch=16, tpatch=1, merge=1,
+                     out_dim=out_dim, use_cls=0, pos="rope2d", max_pos=0, final_ln=0, norm="rms", gated=1)
+
+
+def config8(n_images=16, layers=24, lo=256, hi=1024, with_frames=True, desc=None) -> Workload:
+    """A batch of variable-size images (sides multiples of 16) through the merge-free rotary encoder."""
+    desc = desc or plain_rotary_desc(layers=layers)
+    hs, ws = _dyn_sizes(np.random.default_rng(8), n_images, lo, hi, 16)
+    rng = np.random.default_rng(7)
+    items = [Item(IMAGE, 1, h, w, h, w, random_frames(rng, 1, h, w) if with_frames else None)
+             for h, w in zip(hs, ws)]
+    return Workload("cfg8_varsize16_patch16_nomerge_vit24x1024_proj5120", desc, items)
+
+
 # config 6 runs the config-4 encoder (same weights): only the request structure differs
-WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004, 7: 1007}
+WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004, 7: 1007, 8: 1008}
 
 
 def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> Workload:
@@ -278,7 +296,7 @@ def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> W
         if layers is not None:
             wl.desc.layers = layers
     else:
-        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[idx](with_frames=with_frames, **kw)
+        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7, 8: config8}[idx](with_frames=with_frames, **kw)
     if with_weights:
         wl.weights = make_weights(wl.desc, WEIGHT_SEEDS[idx])
     return wl
@@ -314,6 +332,9 @@ def small_config(idx: int, random_affine=True) -> Workload:
         desc = windowed_desc(layers=4, d=320, heads=4, mlp=640, out_dim=192, window=4, full_every=2)
         wl = config5(n_videos=1, n_images=3, n_text=2, video_frames=4, video_side=112, lo=56, hi=196,
                      src_lo=60, src_hi=200, desc=desc)
+    elif idx == 8:
+        desc = plain_rotary_desc(layers=2, d=256, heads=4, mlp=512, out_dim=192)
+        wl = config8(n_images=4, lo=48, hi=240, desc=desc)
     else:
         raise ValueError(idx)
     wl.name = f"small{idx}"
