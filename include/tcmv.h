@@ -236,7 +236,8 @@ int tcmv_op_layernorm(int dtype, const float *d_x, const float *d_gamma, const f
 
 /* C = epilogue(A * W^T + bias).  A [m, k], W [n, k], both bf16 (k % 64 == 0,
  * n % 8 == 0) or fp32.  epilogue: 0: store (bf16 / fp32 by dtype);
- * 1: GELU (erf form) then store; 2: d_c is fp32 [m, n] and is incremented
+ * 1: GELU (erf form; the bf16 path evaluates it to within 3e-5 absolute) then
+ * store; 2: d_c is fp32 [m, n] and is incremented
  * (residual add); 5 (TCMV_BF16 only): gated product, output column j =
  * silu(column 2j) * column 2j+1, d_c is bf16 [m, n/2].  bias fp32 [n] or NULL. */
 int tcmv_op_gemm(int dtype, int epilogue, const void *d_a, const void *d_w, const float *d_bias,

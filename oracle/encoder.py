@@ -42,10 +42,14 @@ returns V; zero queries return mean(V); agreement with a pure-Python triple
 loop (oracle/naive.py); permutation equivariance without position terms;
 segment independence; LN output statistics; GELU identities and tabulated erf
 values; L=0 reduces to one library GEMM; zeroed W_o / W_2 make blocks the
-identity; merge view against a brute-force gather.  There are no published
-output values for any encoder in the paper: beyond these pins the encoder
-output rests on "oracle == definition" (parity unpinned against the outside
-world).
+identity; merge view against a brute-force gather; and the whole path frames ->
+hidden -> projector output against models put together from torch.nn library
+modules only (Conv2d / Conv3d patch embedding, nn.TransformerEncoder with
+norm_first and exact GELU, nn.LayerNorm, unfold for the 2x2 grouping), for the
+CLS + learned-position family, the separable-position video family and the
+2x2-merge + projector family.  The variant switches have their own pins
+(tests/test_oracle_variants.py).  The paper prints no output values of any
+encoder, so there is nothing of the paper's to compare with beyond these.
 """
 from __future__ import annotations
 

@@ -258,3 +258,121 @@ def test_threaded_heads_give_identical_results():
     q, k, v = _rand(rng, 50, 48), _rand(rng, 50, 48), _rand(rng, 50, 48)
     cu = [0, 13, 50]
     assert np.array_equal(oe.attention(q, k, v, cu, 4), oe.attention(q, k, v, cu, 4, workers=3))
+
+
+@pytest.mark.parametrize("kind", ["image_cls_learned", "video_sep2d"])
+def test_whole_encoder_against_torch_transformer(kind):
+    """The whole path frames -> hidden against a model put together from torch.nn library modules only:
+    Conv2d / Conv3d with kernel = stride = patch as the patch embedding (which also fixes the element
+    order inside a patch row and the raster order of the rows), nn.TransformerEncoder with
+    norm_first=True and exact GELU as the blocks, nn.LayerNorm as the final norm."""
+    rng = np.random.default_rng(5)
+    if kind == "image_cls_learned":
+        desc = workloads.ModelDesc(dtype="f32", layers=3, d=64, heads=4, mlp=128, patch=16, tpatch=1, merge=1, use_cls=1,
+                         pos="learned1d", max_pos=13, final_ln=1)
+        frames = workloads.random_frames(rng, 1, 48, 64)
+        item = workloads.Item(workloads.IMAGE, 1, 48, 64, 48, 64, frames)
+    else:
+        desc = workloads.ModelDesc(dtype="f32", layers=2, d=48, heads=3, mlp=96, patch=8, tpatch=2, merge=1, use_cls=0,
+                         pos="sep2d", max_pos=6, final_ln=0)
+        frames = workloads.random_frames(rng, 4, 24, 40)
+        item = workloads.Item(workloads.VIDEO, 4, 24, 40, 24, 40, frames)
+    w = workloads.make_weights(desc, 77, random_affine=True)
+    wl = workloads.Workload(kind, desc, [item], w)
+    got = oracle.run(wl, dtype=np.float64)["hidden"]
+
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    d, P, tp = desc.d, desc.patch, desc.tpatch
+    mean, std = t(desc.mean).view(1, 3, 1, 1), t(desc.std).view(1, 3, 1, 1)
+    x = (t(frames).permute(0, 3, 1, 2) / 255.0 - mean) / std          # [n, 3, H, W]
+    x = x.float().double()                                            # the stage stores fp32 patch values
+    if tp == 1:
+        conv = torch.nn.Conv2d(3, d, P, stride=P, dtype=torch.float64)
+        conv.weight.data = t(w["w_pe"][:, :desc.k]).view(d, 3, P, P)
+        conv.bias.data = t(w["b_pe"])
+        tok = conv(x).flatten(2).transpose(1, 2)                      # [1, gh*gw, d], rows in (h, w) order
+    else:
+        conv = torch.nn.Conv3d(3, d, (tp, P, P), stride=(tp, P, P), dtype=torch.float64)
+        conv.weight.data = t(w["w_pe"][:, :desc.k]).view(d, 3, tp, P, P)
+        conv.bias.data = t(w["b_pe"])
+        vol = x.permute(1, 0, 2, 3).unsqueeze(0)                      # [1, 3, n, H, W]
+        tok = conv(vol).flatten(2).transpose(1, 2)                    # rows in (t, h, w) order
+    if desc.use_cls:
+        tok = torch.cat([t(w["cls"]).view(1, 1, d), tok], 1)
+        tok = tok + t(w["pos0"])[: tok.shape[1]].unsqueeze(0)
+    else:
+        gt, gh, gw = frames.shape[0] // tp, frames.shape[1] // P, frames.shape[2] // P
+        pos = (t(w["pos0"])[:gh, None, :] + t(w["pos1"])[None, :gw, :]).reshape(1, gh * gw, d).repeat(1, gt, 1)
+        tok = tok + pos
+    layer = torch.nn.TransformerEncoderLayer(d, desc.heads, desc.mlp, dropout=0.0, activation="gelu",
+                                             layer_norm_eps=desc.ln_eps, batch_first=True, norm_first=True,
+                                             dtype=torch.float64)
+    final = torch.nn.LayerNorm(d, eps=desc.ln_eps, dtype=torch.float64) if desc.final_ln else None
+    model = torch.nn.TransformerEncoder(layer, desc.layers, norm=final, enable_nested_tensor=False)
+    for l, lay in enumerate(model.layers):
+        g = lambda k: t(w[f"l{l}.{k}"])
+        lay.self_attn.in_proj_weight.data, lay.self_attn.in_proj_bias.data = g("w_qkv"), g("b_qkv")
+        lay.self_attn.out_proj.weight.data, lay.self_attn.out_proj.bias.data = g("w_o"), g("b_o")
+        lay.linear1.weight.data, lay.linear1.bias.data = g("w_1"), g("b_1")
+        lay.linear2.weight.data, lay.linear2.bias.data = g("w_2"), g("b_2")
+        lay.norm1.weight.data, lay.norm1.bias.data = g("ln1_g"), g("ln1_b")
+        lay.norm2.weight.data, lay.norm2.bias.data = g("ln2_g"), g("ln2_b")
+    if final is not None:
+        final.weight.data, final.bias.data = t(w["lnf_g"]), t(w["lnf_b"])
+    model.eval()
+    with torch.no_grad():
+        ref = model(tok)[0].numpy()
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+
+
+def test_merged_family_against_torch_modules_and_unfold():
+    """The 2x2-merge family end to end (frames -> hidden -> projector output): Conv3d patch embedding and
+    nn.TransformerEncoder on raster-ordered tokens, then torch.nn.functional.unfold (kernel = stride = 2) as
+    the library's own definition of the 2x2 grouping; the reference's rows come in merge-group order, so its
+    hidden matrix viewed as [T/4, 4d] must equal the unfolded raster result group by group."""
+    rng = np.random.default_rng(6)
+    desc = workloads.ModelDesc(dtype="f32", layers=2, d=32, heads=2, mlp=64, patch=8, tpatch=2, merge=2, out_dim=40,
+                               use_cls=0, pos="sep2d", max_pos=6, final_ln=0)
+    frames = workloads.random_frames(rng, 4, 32, 48)
+    w = workloads.make_weights(desc, 78, random_affine=True)
+    wl = workloads.Workload("merged", desc, [workloads.Item(workloads.VIDEO, 4, 32, 48, 32, 48, frames)], w)
+    res = oracle.run(wl, dtype=np.float64)
+
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    d, P, tp = desc.d, desc.patch, desc.tpatch
+    gt, gh, gw = 2, 4, 6
+    x = ((t(frames).permute(0, 3, 1, 2) / 255.0 - 0.5) / 0.5).float().double()
+    conv = torch.nn.Conv3d(3, d, (tp, P, P), stride=(tp, P, P), dtype=torch.float64)
+    conv.weight.data, conv.bias.data = t(w["w_pe"][:, :desc.k]).view(d, 3, tp, P, P), t(w["b_pe"])
+    tok = conv(x.permute(1, 0, 2, 3).unsqueeze(0)).flatten(2).transpose(1, 2)          # [1, gt*gh*gw, d] raster
+    pos = (t(w["pos0"])[:gh, None, :] + t(w["pos1"])[None, :gw, :]).reshape(1, gh * gw, d).repeat(1, gt, 1)
+    layer = torch.nn.TransformerEncoderLayer(d, desc.heads, desc.mlp, dropout=0.0, activation="gelu",
+                                             layer_norm_eps=desc.ln_eps, batch_first=True, norm_first=True,
+                                             dtype=torch.float64)
+    model = torch.nn.TransformerEncoder(layer, desc.layers, enable_nested_tensor=False)
+    for l, lay in enumerate(model.layers):
+        g = lambda k: t(w[f"l{l}.{k}"])
+        lay.self_attn.in_proj_weight.data, lay.self_attn.in_proj_bias.data = g("w_qkv"), g("b_qkv")
+        lay.self_attn.out_proj.weight.data, lay.self_attn.out_proj.bias.data = g("w_o"), g("b_o")
+        lay.linear1.weight.data, lay.linear1.bias.data = g("w_1"), g("b_1")
+        lay.linear2.weight.data, lay.linear2.bias.data = g("w_2"), g("b_2")
+        lay.norm1.weight.data, lay.norm1.bias.data = g("ln1_g"), g("ln1_b")
+        lay.norm2.weight.data, lay.norm2.bias.data = g("ln2_g"), g("ln2_b")
+    model.eval()
+
+    def groups(h):          # [gt*gh*gw, d] raster -> [gt*(gh/2)*(gw/2), 4*d], group rows ordered (h%2, w%2)
+        img = h.view(gt, gh, gw, d).permute(0, 3, 1, 2)                                 # [gt, d, gh, gw]
+        u = torch.nn.functional.unfold(img, kernel_size=2, stride=2)                    # [gt, d*4, L], (c, kh, kw)
+        return u.view(gt, d, 4, -1).permute(0, 3, 2, 1).reshape(-1, 4 * d)
+
+    with torch.no_grad():
+        hid = model(tok + pos)[0]
+        ref_hidden = groups(hid).numpy()
+        y = torch.nn.functional.layer_norm(hid, (d,), t(w["lnm_g"]), t(w["lnm_b"]), desc.ln_eps)
+        y = torch.nn.functional.gelu(torch.nn.functional.linear(groups(y), t(w["w_m1"]), t(w["b_m1"])))
+        ref_out = torch.nn.functional.linear(y, t(w["w_m2"]), t(w["b_m2"])).numpy()
+    got_hidden = res["hidden"].reshape(-1, 4 * d)
+    assert got_hidden.shape == ref_hidden.shape and res["out"].shape == ref_out.shape
+    assert np.abs(got_hidden - ref_hidden).max() <= 1e-9 * max(1.0, np.abs(ref_hidden).max())
+    assert np.abs(res["out"] - ref_out).max() <= 1e-9 * max(1.0, np.abs(ref_out).max())
