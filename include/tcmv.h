@@ -176,7 +176,10 @@ int tcmv_set_weights(tcmv_ctx *ctx, const tcmv_weights *w);
  * work list.  TCMV_E_BAD_SHAPE: dst not a positive multiple of patch*merge,
  * video length not a multiple of tpatch, src size < 1 for an item with frames,
  * a segment longer than max_pos rows (LEARNED_1D) or a grid side above max_pos
- * (SEPARABLE_2D).  Zero items, or only text items, give a valid empty plan. */
+ * (SEPARABLE_2D), a grid side above 255, or so many tokens that tokens x widest
+ * activation row (max of 3d, mlp, merge^2 d, k_pad) reaches 2^32 (the kernels keep
+ * element offsets in 32 bits; about 838 000 tokens at mlp = 5120).  Zero items,
+ * or only text items, give a valid empty plan. */
 int tcmv_plan_create(tcmv_ctx *ctx, const tcmv_item *items, int n_items, tcmv_plan **out);
 void tcmv_plan_destroy(tcmv_plan *plan);
 int tcmv_plan_query(const tcmv_plan *plan, tcmv_plan_info *info);

@@ -467,6 +467,13 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   }
   p->n_patch_rows = (int64_t)p->prow_item.size();
   p->n_tokens = p->cu.back();
+  {
+    // the kernels keep element offsets into the activation matrices in 32 bits
+    const int64_t m2 = (int64_t)d.merge * d.merge;
+    const int64_t widest = std::max<int64_t>({3LL * d.d, (int64_t)d.mlp, m2 * d.d, k_pad_of(d)});
+    if ((double)(p->t_vpad + kVtAlign) * (double)widest >= 4294967296.0)
+      return bad("too many tokens in one plan: tokens x widest activation row (max of 3d, mlp, merge^2 d, k_pad) must stay below 2^32");
+  }
   p->n_segments = (int)seg_start.size();
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads, seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
@@ -837,6 +844,8 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
   std::vector<AttnWork> work;
   const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work, &rseg);
   if (L.T == 0) return TCMV_OK;
+  // the kernels keep element offsets into qkv and into the transposed values in 32 bits
+  if ((double)(L.t_vpad + kVtAlign) * 3.0 * (double)d >= 4294967296.0) return TCMV_E_UNSUPPORTED;
   if (!d_qkv || !d_out || !d_workspace) return TCMV_E_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return TCMV_E_INVALID_ARG;
   if (workspace_bytes < L.total) return TCMV_E_WORKSPACE_TOO_SMALL;

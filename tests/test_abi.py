@@ -138,6 +138,14 @@ def test_bad_shapes_are_rejected():
     for items in ([], [I(0, 0, 0, 0, 0, 0)] * 3):
         pl = enc.plan(items, upload=False)
         assert pl.info.n_tokens == 0 and pl.info.n_patch_rows == 0 and pl.cu_seqlens == [0] * (len(items) + 1)
+    # more tokens than the kernels' 32-bit element offsets allow (tokens x widest row below 2^32): 14 images of
+    # 254 x 254 patches with rows up to 5120 wide; one fewer image fits
+    big = workloads.qwen_like_desc(layers=1, max_grid=254)
+    side = 254 * 14
+    with pytest.raises(B.TcmvError) as e:
+        VisionEncoder(big).plan([I(1, 1, side, side, side, side)] * 14, upload=False)
+    assert e.value.code == B.TCMV_E_BAD_SHAPE and "2^32" in str(e.value)
+    assert VisionEncoder(big).plan([I(1, 1, side, side, side, side)] * 12, upload=False).info.n_tokens == 12 * 254 * 254
     # learned 1-D table too short
     d2 = workloads.ModelDesc(dtype="bf16", layers=1, d=128, heads=2, mlp=128, patch=14, pos="learned1d", max_pos=3)
     with pytest.raises(B.TcmvError) as e:
