@@ -61,12 +61,20 @@ def test_full_preprocess_bit_exact(idx):
     assert row == pl.info.n_patch_rows
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70, 8])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70, 8, 40])
 def test_full_token_count_one_layer_sampled_rows(idx):
     if idx == 70:                      # the windowed family's full-attention layer (rotary positions, 32768 keys)
         idx = 7
         wl = workloads.full_config(7, layers=1)
         wl.desc.full_every = 1
+    elif idx == 40:                    # the longest segment a single image can give: 252 x 252 patches, 63504 keys
+        desc = workloads.qwen_like_desc(layers=1, max_grid=252)
+        rng = np.random.default_rng(40)
+        side = 252 * 14
+        wl = workloads.Workload("one_image_252x252_patches", desc,
+                                [workloads.Item(workloads.IMAGE, 1, side, side, side, side,
+                                                workloads.random_frames(rng, 1, side, side))],
+                                workloads.make_weights(desc, 1040))
     else:
         wl = workloads.full_config(idx, layers=1)
     desc, w = wl.desc, wl.weights
