@@ -213,7 +213,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7, 8])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 7, 8, 9])
     ap.add_argument("--layers", type=int, default=None, help="override depth (not a valid headline number)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-reference timing")
     ap.add_argument("--per-request", action="store_true",

@@ -77,7 +77,8 @@ typedef enum { TCMV_NORM_LAYER = 0, TCMV_NORM_RMS = 1 } tcmv_norm;
 typedef enum { TCMV_TEXT = 0, TCMV_IMAGE = 1, TCMV_VIDEO = 2 } tcmv_modality;
 
 /* Encoder description.  d % heads == 0; head size d/heads must be a multiple
- * of 16 and at most 128; d, mlp and out_dim multiples of 64 for TCMV_BF16. */
+ * of 16 and at most 128 (TCMV_F32) or one of 32, 64, 80, 96 (TCMV_BF16); d, mlp
+ * and heads*head size multiples of 64, out_dim of 8 for TCMV_BF16. */
 typedef struct {
   int dtype;       /* tcmv_dtype */
   int layers, d, heads, mlp;
@@ -109,6 +110,13 @@ typedef struct {
                       and k are rotated; the first dh/4 pairs by
                       h * theta^(-p/(dh/4)), the others by w * theta^(-(p-dh/4)/(dh/4)),
                       (h, w) = patch coordinate of the token; dh % 4 == 0        */
+  int head_dim;    /* 0: every head is d/heads wide.  > 0 (TCMV_BF16 only): size of a head
+                      as stored; q, k, v are then heads*head_dim wide each: w_qkv
+                      [3*heads*head_dim, d], b_qkv [3*heads*head_dim], w_o
+                      [d, heads*head_dim].  A model whose head size the kernels do not
+                      have (72, say) is run by zero-padding every head to the next
+                      size they have and giving the true scale in attn_scale        */
+  float attn_scale; /* 0: scores are scaled by 1/sqrt(head size); > 0: by this value */
 } tcmv_model_desc;
 
 /* One request.  Text requests carry no frames (n_frames == 0), produce no
@@ -151,7 +159,8 @@ typedef struct {
   int n_items, n_segments;       /* n_segments: items with at least one token         */
 } tcmv_plan_info;
 
-/* major*100 + minor; 110 added the encoder-family fields at the end of tcmv_model_desc. */
+/* major*100 + minor; 110 added the encoder-family fields at the end of tcmv_model_desc,
+ * 120 head_dim and attn_scale behind them. */
 int tcmv_version(void);
 const char *tcmv_error_name(int code);
 

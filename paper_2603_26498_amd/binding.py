@@ -27,7 +27,7 @@ class tcmv_model_desc(C.Structure):
                 ("use_cls", C.c_int), ("pos", C.c_int), ("max_pos", C.c_int), ("final_ln", C.c_int),
                 ("ln_eps", C.c_float), ("mean", C.c_float * 3), ("std", C.c_float * 3),
                 ("norm", C.c_int), ("mlp_gated", C.c_int), ("window", C.c_int), ("full_every", C.c_int),
-                ("rope_theta", C.c_float)]
+                ("rope_theta", C.c_float), ("head_dim", C.c_int), ("attn_scale", C.c_float)]
 
 
 class tcmv_item(C.Structure):
@@ -110,7 +110,7 @@ def error_name(code: int) -> str:
 
 def make_desc(dtype="bf16", layers=0, d=0, heads=1, mlp=0, patch=14, tpatch=1, merge=1, out_dim=0, use_cls=0,
               pos="none", max_pos=0, final_ln=0, ln_eps=1e-6, mean=(0.5, 0.5, 0.5), std=(0.5, 0.5, 0.5),
-              norm="layer", gated=0, window=0, full_every=0, rope_theta=10000.0):
+              norm="layer", gated=0, window=0, full_every=0, rope_theta=10000.0, head_dim=0, attn_scale=0.0):
     m = tcmv_model_desc()
     m.dtype = {"f32": TCMV_F32, "bf16": TCMV_BF16}[dtype] if isinstance(dtype, str) else int(dtype)
     m.layers, m.d, m.heads, m.mlp = layers, d, heads, mlp
@@ -120,6 +120,7 @@ def make_desc(dtype="bf16", layers=0, d=0, heads=1, mlp=0, patch=14, tpatch=1, m
     m.norm = {"layer": 0, "rms": 1}[norm] if isinstance(norm, str) else int(norm)
     m.mlp_gated, m.window, m.full_every, m.rope_theta = int(gated), int(window), int(full_every), float(rope_theta)
     m.max_pos, m.final_ln, m.ln_eps = max_pos, final_ln, ln_eps
+    m.head_dim, m.attn_scale = int(head_dim), float(attn_scale)
     for i in range(3):
         m.mean[i] = mean[i]
         m.std[i] = std[i]

@@ -91,6 +91,13 @@ float round_bf16_host(float f) {
   return f;
 }
 
+// size of one head as stored in w_qkv / w_o, width of the attention (heads * head size), softmax scale
+int head_dim_of(const tcmv_model_desc& d) { return d.head_dim > 0 ? d.head_dim : d.d / d.heads; }
+int attn_width_of(const tcmv_model_desc& d) { return d.heads * head_dim_of(d); }
+double attn_scale_of(const tcmv_model_desc& d) {
+  return d.attn_scale > 0.f ? (double)d.attn_scale : 1.0 / std::sqrt((double)head_dim_of(d));
+}
+
 int validate_desc(const tcmv_model_desc* d, std::string& why) {
   if (!d) { why = "null description"; return TCMV_E_INVALID_ARG; }
   if (d->dtype != TCMV_F32 && d->dtype != TCMV_BF16) { why = "unknown dtype"; return TCMV_E_INVALID_ARG; }
@@ -102,7 +109,8 @@ int validate_desc(const tcmv_model_desc* d, std::string& why) {
       d->window < 0 || d->full_every < 0) { why = "bad encoder-family switch"; return TCMV_E_INVALID_ARG; }
   if (d->window % d->merge) { why = "window must be a multiple of merge"; return TCMV_E_INVALID_ARG; }
   if (d->pos == TCMV_POS_ROTARY_2D && !(d->rope_theta > 0.f && std::isfinite(d->rope_theta))) { why = "rope_theta must be positive"; return TCMV_E_INVALID_ARG; }
-  if (d->d % d->heads) { why = "d not divisible by heads"; return TCMV_E_INVALID_ARG; }
+  if (d->head_dim < 0 || !(d->attn_scale >= 0.f) || !std::isfinite(d->attn_scale)) { why = "negative head_dim or attn_scale"; return TCMV_E_INVALID_ARG; }
+  if (d->head_dim == 0 && d->d % d->heads) { why = "d not divisible by heads"; return TCMV_E_INVALID_ARG; }
   if (!(d->ln_eps >= 0.f)) { why = "negative ln_eps"; return TCMV_E_INVALID_ARG; }
   for (int c = 0; c < 3; ++c)
     if (!(d->std[c] > 0.f) || !std::isfinite(d->mean[c])) { why = "bad mean/std"; return TCMV_E_INVALID_ARG; }
@@ -111,7 +119,8 @@ int validate_desc(const tcmv_model_desc* d, std::string& why) {
   if (d->out_dim && d->use_cls) { why = "projector with CLS rows"; return TCMV_E_UNSUPPORTED; }
   if (d->patch > 32) { why = "patch above 32"; return TCMV_E_UNSUPPORTED; }
   if (d->d % 4 || d->d > 2048) { why = "d must be a multiple of 4, at most 2048"; return TCMV_E_UNSUPPORTED; }
-  const int dh = d->d / d->heads;
+  const int dh = head_dim_of(*d);
+  if (d->head_dim && d->dtype != TCMV_BF16) { why = "an explicit head size needs the bf16 path"; return TCMV_E_UNSUPPORTED; }
   if (d->norm || d->mlp_gated || d->window || d->pos == TCMV_POS_ROTARY_2D) {
     if (d->dtype != TCMV_BF16) { why = "RMSNorm, gated MLP, windows and rotary positions need the bf16 path"; return TCMV_E_UNSUPPORTED; }
     if (d->use_cls) { why = "RMSNorm, gated MLP, windows and rotary positions are defined without CLS rows"; return TCMV_E_UNSUPPORTED; }
@@ -119,7 +128,7 @@ int validate_desc(const tcmv_model_desc* d, std::string& why) {
   }
   if (d->dtype == TCMV_BF16) {
     if (dh != 32 && dh != 64 && dh != 80 && dh != 96) { why = "bf16 head size must be 32, 64, 80 or 96"; return TCMV_E_UNSUPPORTED; }
-    if (d->d % 64 || d->mlp % 64 || d->out_dim % 8) { why = "bf16 path needs d, mlp multiples of 64 and out_dim of 8"; return TCMV_E_UNSUPPORTED; }
+    if (d->d % 64 || d->mlp % 64 || d->out_dim % 8 || (d->heads * dh) % 64) { why = "bf16 path needs d, mlp and heads*head size multiples of 64 and out_dim of 8"; return TCMV_E_UNSUPPORTED; }
   } else {
     if (dh % 16 || dh > 128) { why = "fp32 head size must be a multiple of 16, at most 128"; return TCMV_E_UNSUPPORTED; }
   }
@@ -141,10 +150,11 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   const size_t T = (size_t)p->n_tokens;
   EncodeWs w{};
   size_t off = 0;
-  w.xn = off; off = align_up(off + T * d.d * e, 256);
+  const size_t da = (size_t)attn_width_of(d);
+  w.xn = off; off = align_up(off + T * std::max<size_t>(d.d, da) * e, 256);   // LN output [T, d], then attention output [T, da]
   if (d.dtype == TCMV_BF16) {
-    w.qkv = off; off = align_up(off + T * 2 * d.d * e, 256);
-    w.vt = off; off = align_up(off + (size_t)d.d * p->ldvt() * e, 256);
+    w.qkv = off; off = align_up(off + T * 2 * da * e, 256);
+    w.vt = off; off = align_up(off + da * p->ldvt() * e, 256);
   } else {
     w.qkv = off; off = align_up(off + T * 3 * d.d * e, 256);
     w.vt = off;
@@ -261,7 +271,7 @@ hipError_t run_gemm(const tcmv_ctx* ctx, const GemmArgs& g, hipStream_t s) {
 
 extern "C" {
 
-int tcmv_version(void) { return 110; }   // 110: tcmv_model_desc gained the encoder-family switches
+int tcmv_version(void) { return 120; }   // 110: tcmv_model_desc gained the encoder-family switches; 120: head_dim, attn_scale
 
 const char* tcmv_error_name(int code) {
   switch (code) {
@@ -362,7 +372,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->ctx = ctx;
   p->cu.assign(1, 0);
   std::vector<int64_t> seg_start, seg_len, seg_v0, win_start, win_len, win_v0;
-  const int dh_ = d.d / d.heads;
+  const int dh_ = head_dim_of(d);
   std::vector<double> rope_freq;      // theta^(-j/(dh/4)), j < dh/4
   if (d.pos == TCMV_POS_ROTARY_2D)
     for (int j = 0; j < dh_ / 4; ++j) rope_freq.push_back(std::pow((double)d.rope_theta, -(double)j / (double)(dh_ / 4)));
@@ -470,12 +480,12 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   {
     // the kernels keep element offsets into the activation matrices in 32 bits
     const int64_t m2 = (int64_t)d.merge * d.merge;
-    const int64_t widest = std::max<int64_t>({3LL * d.d, (int64_t)d.mlp, m2 * d.d, k_pad_of(d)});
+    const int64_t widest = std::max<int64_t>({3LL * d.d, 3LL * attn_width_of(d), (int64_t)d.mlp, m2 * d.d, k_pad_of(d)});
     if ((double)(p->t_vpad + kVtAlign) * (double)widest >= 4294967296.0)
       return bad("too many tokens in one plan: tokens x widest activation row (max of 3d, mlp, merge^2 d, k_pad) must stay below 2^32");
   }
   p->n_segments = (int)seg_start.size();
-  p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(d.d / d.heads, seg_len) : kAttnBQ_f32;
+  p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
   // The key-norm pass costs one read of K per layer; what it can save grows with the number of keys per query.
@@ -609,13 +619,14 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   void* hbuf = wsb + ws.h;
   float* x = reinterpret_cast<float*>(d_hidden);
   const int64_t T = p->n_tokens;
-  const int dh = d.d / d.heads;
+  const int dh = head_dim_of(d);
+  const int da = attn_width_of(d);               // width of q, k, v and of the attention output (= d unless head_dim is set)
   hipError_t e;
 #define TCMV_CHECK(call, what) do { e = (call); if (e != hipSuccess) return fail_hip(ctx, e, what); } while (0)
 
   // the padding columns of the transposed-V buffer must read as zeros in every layer
   if (bf)
-    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)d.d * p->ldvt() * 2, s); }), "V^T clear");
+    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)da * p->ldvt() * 2, s); }), "V^T clear");
   // patch embedding (+ position), CLS rows
   {
     GemmArgs g{};
@@ -639,14 +650,14 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
     TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s, d.norm); }), "LN1");
     {
       GemmArgs g{};
-      g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * d.d; g.k = d.d;
+      g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * da; g.k = d.d;
       g.c = qkv; g.epi = EPI_QKV;
       if (bf) {
-        g.ldc = 2 * d.d; g.split = 2 * d.d; g.vt = vt; g.ldvt = p->ldvt();
+        g.ldc = 2 * da; g.split = 2 * da; g.vt = vt; g.ldvt = p->ldvt();
         g.vcol = dev<int32_t>(p, windowed ? p->off_vcol_win : p->off_vcol);
         if (d.pos == TCMV_POS_ROTARY_2D) { g.rope = dev<float>(p, p->off_rope); g.rope_dh = dh; }
         // the queries leave the projection already multiplied by softmax scale * log2(e)
-        g.qcols = d.d; g.qscale = (float)(1.4426950408889634 / std::sqrt((double)dh));
+        g.qcols = da; g.qscale = (float)(1.4426950408889634 * attn_scale_of(d));
       }
       else { g.ldc = 3 * d.d; }
       TCMV_CHECK(timed(ctx, TCMV_K_QKV_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "QKV GEMM");
@@ -655,11 +666,11 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       AttnArgs a{};
       if (windowed) { a.work = dev<AttnWork>(p, p->off_work_win); a.n_work = (int)p->work_win.size(); }
       else { a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size(); }
-      a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = d.d;
+      a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = da;
       a.bq = windowed ? kAttnBQ_window : p->bq;
       if (bf) {
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
-        a.q = qk; a.k = qk + d.d; a.ldqk = 2 * d.d; a.v = vt; a.ldv = p->ldvt();
+        a.q = qk; a.k = qk + da; a.ldqk = 2 * da; a.v = vt; a.ldv = p->ldvt();
         a.scale = 1.0f; a.prescaled = 1;
         // largest key norm per (segment, head): lets the attention kernel drop the running maximum where
         // the scores are provably small
@@ -667,7 +678,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
           uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
           TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
           TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
-                       return launch_knorm(qk + d.d, 2 * d.d, T, d.heads, dh,
+                       return launch_knorm(qk + da, 2 * da, T, d.heads, dh,
                                            dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
                      "key norms");
           a.kmax2 = kmax;
@@ -677,13 +688,13 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       } else {
         const float* q3 = reinterpret_cast<const float*>(qkv);
         a.q = q3; a.k = q3 + d.d; a.ldqk = 3 * d.d; a.v = q3 + 2 * d.d; a.ldv = 3 * d.d;
-        a.scale = (float)(1.0 / std::sqrt((double)dh));
+        a.scale = (float)attn_scale_of(d);
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_f32(a, s); }), "attention");
       }
     }
     {
       GemmArgs g{};
-      g.a = xn; g.lda = d.d; g.w = L[4]; g.bias = f(5); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.d;
+      g.a = xn; g.lda = da; g.w = L[4]; g.bias = f(5); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = da;
       g.epi = EPI_RESID;
       TCMV_CHECK(timed(ctx, TCMV_K_OUT_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "out-proj GEMM");
     }

@@ -53,7 +53,21 @@ class VisionEncoder:
 
     def __init__(self, desc, weights: Optional[Dict[str, np.ndarray]] = None, device="cuda:0"):
         self.desc = desc
-        self.cdesc = B.make_desc(dtype=desc.dtype, layers=desc.layers, d=desc.d, heads=desc.heads, mlp=desc.mlp,
+        # Sizes the kernels do not have are reached by zero padding at upload (a layout step: padded q/k
+        # elements add nothing to a score, padded v columns and mlp units meet zero weights afterwards):
+        # a bf16 head size outside {32, 64, 80, 96} goes to the next one up, with the true softmax scale
+        # handed over; an mlp width that is not a multiple of 64 goes to the next multiple.
+        self.dh = desc.d // desc.heads
+        self.dh_lib, self.mlp_lib, attn_scale = 0, desc.mlp, 0.0
+        if desc.dtype == "bf16":
+            if self.dh not in (32, 64, 80, 96):
+                fits = [h for h in (32, 64, 80, 96) if h >= self.dh]
+                if not fits or getattr(desc, "pos", "none") == "rope2d":
+                    raise ValueError(f"head size {self.dh} is not available on the bf16 path")
+                self.dh_lib, attn_scale = fits[0], 1.0 / float(np.sqrt(self.dh))
+            self.mlp_lib = (desc.mlp + 63) // 64 * 64
+        self.cdesc = B.make_desc(dtype=desc.dtype, layers=desc.layers, d=desc.d, heads=desc.heads, mlp=self.mlp_lib,
+                                 head_dim=self.dh_lib, attn_scale=attn_scale,
                                  patch=desc.patch, tpatch=desc.tpatch, merge=desc.merge, out_dim=desc.out_dim,
                                  use_cls=desc.use_cls, pos=desc.pos, max_pos=desc.max_pos, final_ln=desc.final_ln,
                                  ln_eps=desc.ln_eps, mean=desc.mean, std=desc.std,
@@ -80,6 +94,29 @@ class VisionEncoder:
     def _vec(self, a: np.ndarray) -> torch.Tensor:
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).contiguous()
 
+    def _lib_layout(self, name: str, a: np.ndarray) -> np.ndarray:
+        """One layer parameter in the layout the library takes it in (padding and interleaving only)."""
+        d = self.desc
+        pad_rows = lambda x, n: np.concatenate([x, np.zeros((n - x.shape[0],) + x.shape[1:], x.dtype)], 0) if n > x.shape[0] else x
+        if self.dh_lib and name in ("w_qkv", "b_qkv"):
+            # [3, heads, dh, ...] -> [3, heads, dh_lib, ...] with zero rows behind every head
+            x = a.reshape((3, d.heads, self.dh) + a.shape[1:])
+            z = np.zeros((3, d.heads, self.dh_lib - self.dh) + a.shape[1:], a.dtype)
+            return np.concatenate([x, z], 2).reshape((3 * d.heads * self.dh_lib,) + a.shape[1:])
+        if self.dh_lib and name == "w_o":
+            x = a.reshape(a.shape[0], d.heads, self.dh)
+            z = np.zeros((a.shape[0], d.heads, self.dh_lib - self.dh), a.dtype)
+            return np.concatenate([x, z], 2).reshape(a.shape[0], d.heads * self.dh_lib)
+        if name in ("w_1", "b_1"):
+            if getattr(d, "gated", 0):
+                # gate and up rows interleaved (the caller's array has the gate rows first, then the up rows)
+                g, u = pad_rows(a[:d.mlp], self.mlp_lib), pad_rows(a[d.mlp:], self.mlp_lib)
+                return np.stack([g, u], axis=1).reshape((2 * self.mlp_lib,) + a.shape[1:])
+            return pad_rows(a, self.mlp_lib)
+        if name == "w_2" and self.mlp_lib > d.mlp:
+            return np.concatenate([a, np.zeros((a.shape[0], self.mlp_lib - d.mlp), a.dtype)], 1)
+        return a
+
     def set_weights(self, w: Dict[str, np.ndarray]):
         _require_gpu()
         d = self.desc
@@ -96,11 +133,7 @@ class VisionEncoder:
         for l in range(d.layers):
             for j, name in enumerate(B.LAYER_FIELDS):
                 key = f"l{l}.{name}"
-                a = w[key]
-                if getattr(d, "gated", 0) and name in ("w_1", "b_1"):
-                    # layout the library expects for a gated MLP: gate and up rows interleaved
-                    # (the caller's array has the gate rows first, then the up rows)
-                    a = np.stack([a[:d.mlp], a[d.mlp:]], axis=1).reshape((2 * d.mlp,) + a.shape[1:])
+                a = self._lib_layout(name, w[key])
                 T[key] = self._mat(a) if name.startswith("w_") else self._vec(a)
                 arr[l * 12 + j] = T[key].data_ptr()
         self._layer_arr = arr

@@ -40,7 +40,7 @@ def sample_rows(cu, n_rows_total, per_seg_div, n=24):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5, 6, 7, 8])
+    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5, 6, 7, 8, 9])
     ap.add_argument("--out", default=None)
     ap.add_argument("--workers", type=int, default=1, help="threads over attention heads (arithmetic unchanged)")
     args = ap.parse_args()

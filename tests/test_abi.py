@@ -43,7 +43,7 @@ def test_library_exports_every_scheduler_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24 + 4 * 4 + 4
+    assert C.sizeof(B.tcmv_model_desc) == 13 * 4 + 4 + 24 + 4 * 4 + 4 + 4 + 4
     assert C.sizeof(B.tcmv_item) == 6 * 4 + 8
     assert C.sizeof(B.tcmv_weights) == 14 * 8
 

@@ -37,7 +37,7 @@ def check_patches(wl, ref, patches):
     assert not got[:, k:].any(), "padding columns must be zero"
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("affine", [False, True])
 def test_small_workloads(idx, affine):
     wl = workloads.small_config(idx, random_affine=affine)

@@ -40,7 +40,7 @@ def _sample(cu, n, seed):
     return np.array(sorted(pick), np.int64)
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 8, 9])
 def test_full_preprocess_bit_exact(idx):
     wl = workloads.full_config(idx, with_weights=False, layers=0)
     wl.weights = workloads.make_weights(wl.desc, 1)
@@ -61,7 +61,7 @@ def test_full_preprocess_bit_exact(idx):
     assert row == pl.info.n_patch_rows
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70, 8, 40])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5, 6, 7, 70, 8, 40, 9])
 def test_full_token_count_one_layer_sampled_rows(idx):
     if idx == 70:                      # the windowed family's full-attention layer (rotary positions, 32768 keys)
         idx = 7
@@ -122,7 +122,7 @@ def test_full_size_projector_sampled_rows(idx):
     assert_tokens_close(got, ref, 2e-2, 0.999, f"cfg{idx} projector")
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8, 9])
 def test_full_depth_against_stored_reference_rows(idx):
     path = os.path.join(GOLD, f"full_cfg{idx}.npz")
     if not os.path.exists(path):

@@ -284,8 +284,23 @@ def config8(n_images=16, layers=24, lo=256, hi=1024, with_frames=True, desc=None
     return Workload("cfg8_varsize16_patch16_nomerge_vit24x1024_proj5120", desc, items)
 
 
+def config9(n_images=32, layers=27, side=384, d=1152, heads=16, mlp=4304, with_frames=True) -> Workload:
+    """Fixed-resolution crops through an encoder with the shape of the 400M-parameter fixed-resolution
+    encoder that four of the seven models of Table 1 use: patch 14, 27 x 27 = 729 tokens per 384 x 384
+    crop, d = 1152, 16 heads of 72, mlp 4304, learned positions, final LayerNorm.  Head size and mlp
+    width are not sizes the kernels have: the runtime reaches them by zero padding."""
+    g = side // 14
+    desc = ModelDesc(dtype="bf16", layers=layers, d=d, heads=heads, mlp=mlp, patch=14, tpatch=1, merge=1,
+                     out_dim=0, use_cls=0, pos="learned1d", max_pos=g * g, final_ln=1)
+    rng = np.random.default_rng(9)
+    px = g * 14
+    items = [Item(IMAGE, 1, px, px, px, px, random_frames(rng, 1, px, px) if with_frames else None)
+             for _ in range(n_images)]
+    return Workload(f"cfg9_batch{n_images}_crop{px}_vit{layers}x{d}_head72", desc, items)
+
+
 # config 6 runs the config-4 encoder (same weights): only the request structure differs
-WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004, 7: 1007, 8: 1008}
+WEIGHT_SEEDS = {1: 1001, 2: 1002, 3: 1003, 4: 1004, 5: 1005, 6: 1004, 7: 1007, 8: 1008, 9: 1009}
 
 
 def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> Workload:
@@ -296,7 +311,7 @@ def full_config(idx: int, with_frames=True, with_weights=True, layers=None) -> W
         if layers is not None:
             wl.desc.layers = layers
     else:
-        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7, 8: config8}[idx](with_frames=with_frames, **kw)
+        wl = {2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7, 8: config8, 9: config9}[idx](with_frames=with_frames, **kw)
     if with_weights:
         wl.weights = make_weights(wl.desc, WEIGHT_SEEDS[idx])
     return wl
@@ -335,6 +350,8 @@ def small_config(idx: int, random_affine=True) -> Workload:
     elif idx == 8:
         desc = plain_rotary_desc(layers=2, d=256, heads=4, mlp=512, out_dim=192)
         wl = config8(n_images=4, lo=48, hi=240, desc=desc)
+    elif idx == 9:
+        wl = config9(n_images=3, layers=2, side=84, d=576, heads=8, mlp=296)
     else:
         raise ValueError(idx)
     wl.name = f"small{idx}"
