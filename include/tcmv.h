@@ -205,7 +205,8 @@ int64_t tcmv_plan_row_map(const tcmv_plan *plan, int which, const int32_t **out)
 
 /* Stage 1 (Sec. 2.1 "preprocessed into intermediate representations"): resize
  * + normalise + patchify in one pass.  d_patches [n_patch_rows, k_pad], bf16 or
- * fp32 by dtype; every element is written (padding columns with zeros).
+ * fp32 by dtype, 16-byte aligned; every element is written (padding columns
+ * with zeros).
  * Integer / table arithmetic only: results are bit-exact by definition. */
 int tcmv_preprocess(tcmv_ctx *ctx, tcmv_plan *plan, void *d_patches, void *stream);
 

@@ -6,9 +6,10 @@
 //  * strip kernel (requests whose frames need no resampling): a workgroup takes up to
 //    16 horizontally adjacent patches of one patch line, copies their tpatch*patch
 //    source line segments into LDS with coalesced 4-byte loads (every source byte is
-//    read from HBM exactly once), then each thread produces runs from LDS through a
-//    3x256 table of already-rounded normalised values and writes them so that
-//    consecutive lanes write consecutive addresses of a patch row;
+//    read from HBM exactly once, all loads of a thread in flight together), then
+//    produces the patch rows from LDS through a 3x256 table of already-rounded
+//    normalised values; on the bf16 path a wave takes whole rows and its lanes write
+//    consecutive dwords (element pairs) of a row, on the fp32 path a thread writes runs;
 //  * run kernel (resampled requests, or frames that are not 4-byte aligned): one
 //    thread per run, reading its pixels (or the four bilinear taps of each) straight
 //    from global memory.
@@ -113,7 +114,9 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
   constexpr int SEG = kStripTokens * P * 3;              // bytes of one line segment (multiple of 4)
   static_assert(SEG % 4 == 0, "segment size");
   __shared__ float lut[768];
-  __shared__ __attribute__((aligned(16))) uint8_t seg[TP * P][SEG];
+  // lanes that work on neighbouring lines read the same byte offset of each: the line stride is an odd number
+  // of dwords so that those reads fall into different banks
+  __shared__ __attribute__((aligned(16))) uint8_t seg[TP * P][SEG + 4];
   const PreStrip sp = a.strips[blockIdx.x];
   const ItemDev it = a.items[sp.item];
   const int ntok = min(kStripTokens, it.gw - sp.pw0);
@@ -122,13 +125,31 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
   const int nlines = still ? P : TP * P;
   const int row_stride = it.src_w * 3;
   for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
-  // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line
+  // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line.  All loads
+  // of a thread are issued before the first is used (a fixed-count loop over the full strip width, lanes
+  // beyond the strip's own width masked off), so a workgroup has its whole input in flight at once.
   const int ndw = nbytes >> 2;
-  for (int i = threadIdx.x; i < nlines * ndw; i += 256) {
-    const int line = i / ndw, dw = i - line * ndw;
-    const int f = still ? 0 : sp.t * TP + line / P;
-    const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
-    reinterpret_cast<uint32_t*>(seg[line])[dw] = reinterpret_cast<const uint32_t*>(src)[dw];
+  {
+    constexpr int NDW = SEG / 4;                         // dwords of a full-width line segment
+    constexpr int NL = (TP * P * NDW + 255) / 256;       // loads per thread
+    uint32_t v[NL];
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int line = i / NDW, dw = i - line * NDW;
+      v[j] = 0u;
+      if (line < nlines && dw < ndw) {
+        const int f = still ? 0 : sp.t * TP + line / P;
+        const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+        v[j] = reinterpret_cast<const uint32_t*>(src)[dw];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      const int i = threadIdx.x + 256 * j;
+      const int line = i / NDW, dw = i - line * NDW;
+      if (line < nlines && dw < ndw) reinterpret_cast<uint32_t*>(seg[line])[dw] = v[j];
+    }
   }
   const int ntail = nbytes & 3;
   for (int i = threadIdx.x; i < nlines * ntail; i += 256) {
@@ -142,27 +163,64 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
   const int64_t row_line = (a.merge == 2)
       ? (int64_t)it.row0 + ((int64_t)(sp.t * (it.gh >> 1) + (sp.ph >> 1)) * (it.gw >> 1)) * 4 + (sp.ph & 1) * 2
       : (int64_t)it.row0 + (int64_t)(sp.t * it.gh + sp.ph) * it.gw;
-  typedef typename std::conditional<BF16, uint16_t, float>::type out_t;
-  for (int q = threadIdx.x; q < ntok * runs_per_row; q += 256) {
-    const int tok = q / runs_per_row, run = q - tok * runs_per_row;
+  auto row_of = [&](int tok) -> int64_t {
     const int pw = sp.pw0 + tok;
-    const int64_t r = (a.merge == 2) ? row_line + (pw >> 1) * 4 + (pw & 1) : row_line + pw;
-    const int k0 = run * P;
-    out_t* out = reinterpret_cast<out_t*>(a.patches) + (size_t)r * a.k_pad + k0;
-    if (run >= data_runs) {                              // padding columns
-      const int n = min(P, a.k_pad - k0);
-      for (int i = 0; i < n; ++i) out[i] = (out_t)0;
-      continue;
-    }
-    const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
-    const uint8_t* src = seg[(still ? 0 : tt) * P + py] + tok * P * 3 + c;
-    const float* lc = lut + c * 256;
-    if (BF16 && P % 2 == 0) {
-      uint32_t* o2 = reinterpret_cast<uint32_t*>(out);
+    return (a.merge == 2) ? row_line + (pw >> 1) * 4 + (pw & 1) : row_line + pw;
+  };
+  typedef typename std::conditional<BF16, uint16_t, float>::type out_t;
+  if constexpr (BF16 && P % 2 == 0) {
+    // bf16: a lane produces pairs of neighbouring elements (dwords of a patch row) and consecutive lanes
+    // produce consecutive dwords, so every store instruction writes whole cache lines; the padding columns
+    // are dwords like the others.  A wave takes whole tokens, so a lane meets the same dwords of every row
+    // it works on and decodes them (channel, frame, line, pixel pair) once.
+    constexpr int KP = (3 * TP * P * P + 63) / 64 * 64;  // == a.k_pad (checked by the launcher)
+    constexpr int PAIRS = KP / 2;                        // dwords per patch row
+    constexpr int DP = 3 * TP * P * P / 2;               // of which carry pixels
+    constexpr int HP = P / 2;                            // pairs per run
+    constexpr int NJ = (PAIRS + 63) / 64;                // dwords per lane and row
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int soff[NJ], lbase[NJ];                             // byte offset of the pair's first pixel in seg (token 0), table row
 #pragma unroll
-      for (int i = 0; i < P / 2; ++i)
-        o2[i] = (__float_as_uint(lc[src[6 * i]]) >> 16) | (__float_as_uint(lc[src[6 * i + 3]]) & 0xFFFF0000u);
-    } else {
+    for (int j = 0; j < NJ; ++j) {
+      const int e = lane + 64 * j;
+      soff[j] = -1; lbase[j] = 0;
+      if (e < DP) {
+        const int run = e / HP, i = e - run * HP;
+        const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
+        soff[j] = ((still ? 0 : tt) * P + py) * (SEG + 4) + c + 6 * i;
+        lbase[j] = c * 256;
+      }
+    }
+    const uint8_t* seg0 = &seg[0][0];
+    for (int tok = wave; tok < ntok; tok += 4) {
+      const uint8_t* sb = seg0 + tok * P * 3;
+      uint32_t* orow = reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.patches) + (size_t)row_of(tok) * KP);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int e = lane + 64 * j;
+        if (e < PAIRS) {
+          uint32_t val = 0u;
+          if (soff[j] >= 0) {
+            const uint8_t* px = sb + soff[j];
+            val = (__float_as_uint(lut[lbase[j] + px[0]]) >> 16) | (__float_as_uint(lut[lbase[j] + px[3]]) & 0xFFFF0000u);
+          }
+          orow[e] = val;
+        }
+      }
+    }
+  } else {
+    for (int q = threadIdx.x; q < ntok * runs_per_row; q += 256) {
+      const int tok = q / runs_per_row, run = q - tok * runs_per_row;
+      const int k0 = run * P;
+      out_t* out = reinterpret_cast<out_t*>(a.patches) + (size_t)row_of(tok) * a.k_pad + k0;
+      if (run >= data_runs) {                            // padding columns
+        const int n = min(P, a.k_pad - k0);
+        for (int i = 0; i < n; ++i) out[i] = (out_t)0;
+        continue;
+      }
+      const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
+      const uint8_t* src = seg[(still ? 0 : tt) * P + py] + tok * P * 3 + c;
+      const float* lc = lut + c * 256;
 #pragma unroll
       for (int i = 0; i < P; ++i) {
         const float x = lc[src[3 * i]];
@@ -199,6 +257,9 @@ bool preprocess_has_strip_kernel(int patch, int tpatch) {
 hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s) {
   if (a.rows == 0) return hipSuccess;
   if (a.n_strips > 0 && !preprocess_has_strip_kernel(a.patch, a.tpatch)) return hipErrorInvalidValue;
+  // the bf16 strip kernel writes dwords of rows of (K rounded up to 64) elements
+  if (a.n_strips > 0 && a.out_bf16 && (a.k_pad != (a.k + 63) / 64 * 64 || reinterpret_cast<uintptr_t>(a.patches) % 16))
+    return hipErrorInvalidValue;
   if (a.patch > kMaxPatch || a.rows * (int64_t)(3 * a.tpatch * a.patch + a.k_pad) > (1LL << 38)) return hipErrorInvalidValue;
   if (a.patch == 14 && a.tpatch == 2) launch_pp<14, 2>(a, s);
   else if (a.patch == 14 && a.tpatch == 1) launch_pp<14, 1>(a, s);
