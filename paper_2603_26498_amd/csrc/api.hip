@@ -408,10 +408,11 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     const int item_idx = (int)p->items.size();
     di.row0 = (int)p->prow_item.size();
     {
-      // line-by-line copy needs: no resampling, a compiled strip kernel, 4-byte aligned lines
-      const bool strip_ok = !di.resized && d.window == 0 && preprocess_has_strip_kernel(d.patch, d.tpatch) &&
-                            (reinterpret_cast<uintptr_t>(it.d_frames) % 4 == 0) && ((int64_t)it.src_w * 3) % 4 == 0 &&
-                            ((int64_t)it.src_h * it.src_w * 3) % 4 == 0;
+      // the strip kernel needs a compiled patch size and the plain token order; where it copies lines (no
+      // resampling) it also needs them 4-byte aligned
+      const bool aligned = (reinterpret_cast<uintptr_t>(it.d_frames) % 4 == 0) && ((int64_t)it.src_w * 3) % 4 == 0 &&
+                           ((int64_t)it.src_h * it.src_w * 3) % 4 == 0;
+      const bool strip_ok = d.window == 0 && preprocess_has_strip_kernel(d.patch, d.tpatch) && (di.resized || aligned);
       const int64_t n_rows = (int64_t)di.gt * di.gh * di.gw;
       if (strip_ok) {
         for (int t = 0; t < di.gt; ++t)

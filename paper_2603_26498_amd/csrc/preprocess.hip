@@ -3,16 +3,18 @@
 // A patch row is 3*tpatch*patch runs of `patch` consecutive pixels of one channel of
 // one source line, followed by zero padding.  Two kernels share that decomposition:
 //
-//  * strip kernel (requests whose frames need no resampling): a workgroup takes up to
+//  * strip kernel: a workgroup takes up to
 //    16 horizontally adjacent patches of one patch line, copies their tpatch*patch
 //    source line segments into LDS with coalesced 4-byte loads (every source byte is
 //    read from HBM exactly once, all loads of a thread in flight together), then
 //    produces the patch rows from LDS through a 3x256 table of already-rounded
 //    normalised values; on the bf16 path a wave takes whole rows and its lanes write
 //    consecutive dwords (element pairs) of a row, on the fp32 path a thread writes runs;
-//  * run kernel (resampled requests, or frames that are not 4-byte aligned): one
-//    thread per run, reading its pixels (or the four bilinear taps of each) straight
-//    from global memory.
+//    resampled requests go the same way, except that the LDS lines are not copied but
+//    computed: the strip's destination pixels, blended from their four source taps;
+//  * run kernel (frames that are not 4-byte aligned, patch sizes without a compiled
+//    strip kernel, window-major token order): one thread per run, reading its pixels
+//    (or the four bilinear taps of each) straight from global memory.
 //
 // Integer / table arithmetic only: the result is bit-exact by construction.
 #include "tcmv_internal.h"
@@ -125,38 +127,76 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
   const int nlines = still ? P : TP * P;
   const int row_stride = it.src_w * 3;
   for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
-  // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line.  All loads
-  // of a thread are issued before the first is used (a fixed-count loop over the full strip width, lanes
-  // beyond the strip's own width masked off), so a workgroup has its whole input in flight at once.
-  const int ndw = nbytes >> 2;
-  {
-    constexpr int NDW = SEG / 4;                         // dwords of a full-width line segment
-    constexpr int NL = (TP * P * NDW + 255) / 256;       // loads per thread
-    uint32_t v[NL];
+  if (!it.resized) {
+    // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line.  All loads
+    // of a thread are issued before the first is used (a fixed-count loop over the full strip width, lanes
+    // beyond the strip's own width masked off), so a workgroup has its whole input in flight at once.
+    const int ndw = nbytes >> 2;
+    {
+      constexpr int NDW = SEG / 4;                         // dwords of a full-width line segment
+      constexpr int NL = (TP * P * NDW + 255) / 256;       // loads per thread
+      uint32_t v[NL];
 #pragma unroll
-    for (int j = 0; j < NL; ++j) {
-      const int i = threadIdx.x + 256 * j;
-      const int line = i / NDW, dw = i - line * NDW;
-      v[j] = 0u;
-      if (line < nlines && dw < ndw) {
-        const int f = still ? 0 : sp.t * TP + line / P;
-        const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
-        v[j] = reinterpret_cast<const uint32_t*>(src)[dw];
+      for (int j = 0; j < NL; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        const int line = i / NDW, dw = i - line * NDW;
+        v[j] = 0u;
+        if (line < nlines && dw < ndw) {
+          const int f = still ? 0 : sp.t * TP + line / P;
+          const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+          v[j] = reinterpret_cast<const uint32_t*>(src)[dw];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NL; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        const int line = i / NDW, dw = i - line * NDW;
+        if (line < nlines && dw < ndw) reinterpret_cast<uint32_t*>(seg[line])[dw] = v[j];
       }
     }
-#pragma unroll
-    for (int j = 0; j < NL; ++j) {
-      const int i = threadIdx.x + 256 * j;
-      const int line = i / NDW, dw = i - line * NDW;
-      if (line < nlines && dw < ndw) reinterpret_cast<uint32_t*>(seg[line])[dw] = v[j];
+    const int ntail = nbytes & 3;
+    for (int i = threadIdx.x; i < nlines * ntail; i += 256) {
+      const int line = i / ntail, b = (ndw << 2) + (i - line * ntail);
+      const int f = still ? 0 : sp.t * TP + line / P;
+      const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+      seg[line][b] = src[b];
     }
-  }
-  const int ntail = nbytes & 3;
-  for (int i = threadIdx.x; i < nlines * ntail; i += 256) {
-    const int line = i / ntail, b = (ndw << 2) + (i - line * ntail);
-    const int f = still ? 0 : sp.t * TP + line / P;
-    const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
-    seg[line][b] = src[b];
+  } else {
+    // Resampled request: the strip's destination pixels are computed into the same LDS lines (as the uint8
+    // values a resized frame would hold), so everything after this point is shared with the copy case.
+    // Taps and weights of the strip's columns and lines are worked out once per workgroup; a thread then
+    // takes destination pixels with lanes running along the line (neighbouring lanes read neighbouring
+    // source pixels) and blends the three channels of each with the same four weights.
+    __shared__ int col_c0[kStripTokens * P], col_c1[kStripTokens * P], col_fx[kStripTokens * P];
+    __shared__ int line_r0[TP * P], line_r1[TP * P], line_fy[TP * P];
+    const int npx = ntok * P;
+    for (int x = threadIdx.x; x < npx; x += 256) {
+      int c0, c1, fx;
+      axis_tap(sp.pw0 * P + x, it.src_w, it.dst_w, c0, c1, fx);
+      col_c0[x] = c0 * 3; col_c1[x] = c1 * 3; col_fx[x] = fx;
+    }
+    for (int l = threadIdx.x; l < nlines; l += 256) {
+      int r0, r1, fy;
+      axis_tap(sp.ph * P + l % P, it.src_h, it.dst_h, r0, r1, fy);
+      line_r0[l] = r0; line_r1[l] = r1; line_fy[l] = fy;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nlines * npx; i += 256) {
+      const int line = i / npx, x = i - line * npx;
+      const int f = still ? 0 : sp.t * TP + line / P;
+      const uint8_t* fr = it.frames + (size_t)f * it.src_h * it.src_w * 3;
+      const uint8_t* l0 = fr + (size_t)line_r0[line] * row_stride;
+      const uint8_t* l1 = fr + (size_t)line_r1[line] * row_stride;
+      const int c0 = col_c0[x], c1 = col_c1[x], fx = col_fx[x], fy = line_fy[line];
+      const uint32_t w00 = (uint32_t)((kOne - fx) * (kOne - fy)), w01 = (uint32_t)(fx * (kOne - fy));
+      const uint32_t w10 = (uint32_t)((kOne - fx) * fy), w11 = (uint32_t)(fx * fy);
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        const uint32_t acc = (uint32_t)l0[c0 + c] * w00 + (uint32_t)l0[c1 + c] * w01 + (uint32_t)l1[c0 + c] * w10 +
+                             (uint32_t)l1[c1 + c] * w11 + (1u << (2 * kFracBits - 1));
+        seg[line][x * 3 + c] = (uint8_t)(acc >> (2 * kFracBits));
+      }
+    }
   }
   __syncthreads();
   // patch row of token (t, ph, pw): raster order, or merge-group-major order
