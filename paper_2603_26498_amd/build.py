@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtcmv.so")
-SOURCES = ["api.hip", "preprocess.hip", "layernorm.hip", "gemm_bf16.hip", "attn_bf16.hip", "f32_path.hip",
+SOURCES = ["api.hip", "preprocess.hip", "layernorm.hip", "gemm_bf16.hip", "attn_bf16.hip", "attn_window.hip", "f32_path.hip",
            "sched.cpp"]    # sched.cpp is host-only code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

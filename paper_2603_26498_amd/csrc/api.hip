@@ -44,6 +44,7 @@ struct tcmv_plan {
   std::vector<float> rope;            // [n_tokens][dh]: (cos, sin) of every element pair of a head
   std::vector<int32_t> row_seg, row_seg_win;   // hidden row -> index of its segment / window (key-norm table row)
   int n_windows = 0;
+  int64_t max_win_len = 0;          // longest window (tokens)
   std::vector<float> lut;             // [3][256]
   std::vector<PreStrip> strips;       // preprocessing work of requests that are copied line by line
   std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
@@ -499,6 +500,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->norm_bound = d.dtype == TCMV_BF16 && long_enough(seg_len);
   p->norm_bound_win = d.dtype == TCMV_BF16 && long_enough(win_len);
   p->n_windows = (int)win_start.size();
+  for (int64_t n : win_len) p->max_win_len = std::max(p->max_win_len, n);
   // normalisation table: (v/255 - mean)/std in double, rounded to fp32, then to bf16 for bf16 models
   p->lut.resize(3 * 256);
   for (int c = 0; c < 3; ++c)
@@ -673,9 +675,11 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
         const uint16_t* qk = reinterpret_cast<const uint16_t*>(qkv);
         a.q = qk; a.k = qk + da; a.ldqk = 2 * da; a.v = vt; a.ldv = p->ldvt();
         a.scale = 1.0f; a.prescaled = 1;
+        // windows of at most 64 tokens (8 x 8 patches): one small workgroup per window and head
+        const bool short_windows = windowed && p->max_win_len <= 64;
         // largest key norm per (segment, head): lets the attention kernel drop the running maximum where
         // the scores are provably small
-        if (windowed ? p->norm_bound_win : p->norm_bound) {
+        if (!short_windows && (windowed ? p->norm_bound_win : p->norm_bound)) {
           uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
           TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
           TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
@@ -685,7 +689,8 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
           a.kmax2 = kmax;
           a.any_left = kmax + (size_t)std::max(p->n_segments, p->n_windows) * d.heads;
         }
-        TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_attn_bf16(a, s); }), "attention");
+        TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return short_windows ? launch_attn_window_bf16(a, s) : launch_attn_bf16(a, s); }),
+                   "attention");
       } else {
         const float* q3 = reinterpret_cast<const float*>(qkv);
         a.q = q3; a.k = q3 + d.d; a.ldqk = 3 * d.d; a.v = q3 + 2 * d.d; a.ldv = 3 * d.d;

@@ -95,6 +95,8 @@ hipError_t launch_layernorm(const float* x, const float* g, const float* b, void
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
+// windowed layers whose windows hold at most 64 tokens: every work item is one whole window (bf16, prescaled queries)
+hipError_t launch_attn_window_bf16(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t s);
 // vt[c][vcol[r]] = v[r][c] for r < rows, c < d  (bf16)
 hipError_t launch_transpose_v(const void* v, int64_t ldv, const int32_t* vcol, void* vt, int64_t ldvt,

@@ -190,3 +190,22 @@ def test_long_segments_take_the_norm_bounded_attention_path(std):
     assert pl.cu_seqlens == [0, 4096, 4096 + 2304]
     assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], 2e-2, 0.999, "long segments hidden")
     assert_tokens_close(out.float().cpu().numpy(), ref["out"], 2e-2, 0.999, "long segments out")
+
+
+@pytest.mark.parametrize("dh", [80, 64])
+def test_windows_of_up_to_64_tokens_with_ragged_edges(dh):
+    """Windows of 8 x 8 patches on grids that are not multiples of 8: window sizes 64, 48, 32, 24, 16, 8 ... in
+    one batch, every layer windowed (the short-window attention kernel: second wave idle below 33 tokens, keys
+    masked beyond the window), then with every second layer over the whole request."""
+    rng = np.random.default_rng(31)
+    sizes = [(168, 140), (196, 252), (224, 224), (112, 28), (28, 364)]      # patch grids 12x10, 14x18, 16x16, 8x2, 2x26
+    items = [workloads.Item(workloads.IMAGE, 1, h, w, h, w, workloads.random_frames(rng, 1, h, w)) for h, w in sizes]
+    items.insert(2, workloads.Item(workloads.VIDEO, 4, 140, 196, 140, 196, workloads.random_frames(rng, 4, 140, 196)))
+    for full_every in (0, 2):
+        desc = workloads.windowed_desc(layers=2, d=4 * dh, heads=4, mlp=640, out_dim=192, window=8, full_every=full_every)
+        wl = workloads.Workload("ragged_windows", desc, items, workloads.make_weights(desc, 3100 + dh, random_affine=True))
+        ref = oracle.run(wl)
+        enc, pl, patches, hidden, out = run_gpu(wl)
+        check_patches(wl, ref, patches)
+        assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], 2e-2, 0.999, f"ragged windows dh={dh} hidden")
+        assert_tokens_close(out.float().cpu().numpy(), ref["out"], 2e-2, 0.999, f"ragged windows dh={dh} out")
