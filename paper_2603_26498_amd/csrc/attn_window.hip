@@ -14,7 +14,8 @@
 // softmax is the plain one (maximum, exponentials, no running statistics), and the
 // probabilities, packed to bf16 in place, are the B operand of O^T += V^T * P^T.  The
 // queries arrive multiplied by softmax scale * log2(e).  Workgroups that follow each
-// other handle the heads of one window, so the lines of q and k they share are fetched once.
+// other handle the heads of one window, so the lines of q and k they share are fetched once;
+// the output tile leaves through LDS, 16 bytes per lane along a row.
 #include "tcmv_internal.h"
 #include "device_utils.h"
 
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(128) void attn_window_kernel(AttnArgs a) {
   for (int ks = 0; ks < KS; ++ks)
     qf[ks] = *reinterpret_cast<const bf16x8*>(Q + (size_t)(w.q0 + qc) * a.ldqk + head * DH + (2 * ks + lg) * 8);
   __syncthreads();
-  if (wave * 32 >= n) return;                      // nothing for the second wave in a window of at most 32 tokens
+  // (in a window of at most 32 tokens the second wave computes on repeated rows and stores nothing)
 
   // scores: two blocks of 32 keys; a lane holds query lr and keys 32*kb + 8*(v/4) + 4*lg + v%4
   f32x16 s[2];
@@ -134,20 +135,30 @@ __global__ __launch_bounds__(128) void attn_window_kernel(AttnArgs a) {
     l += __shfl_xor(l, 32, 64);
   }
   const float inv = 1.0f / l;
-  if (qi < n) {
-    uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + (size_t)(w.q0 + qi) * a.ldo + head * DH;
+  // The output leaves through LDS so that lanes run along the rows (16 bytes each, whole 2*DH-byte row pieces per
+  // store) instead of writing 8-byte pieces of 32 different rows: each wave puts its 32 x DH tile (bf16) into its
+  // half of the K buffer, which nobody reads any more once both waves are past their scores.
+  __syncthreads();
+  uint8_t* so = sk + wave * 32 * KSTR;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int dh0 = mt * 32 + 8 * vq + 4 * lg;
-        if (dh0 < DH) {
-          uint2 pk;
-          pk.x = pack_bf16x2(o[mt][4 * vq] * inv, o[mt][4 * vq + 1] * inv);
-          pk.y = pack_bf16x2(o[mt][4 * vq + 2] * inv, o[mt][4 * vq + 3] * inv);
-          *reinterpret_cast<uint2*>(op + dh0) = pk;
-        }
+    for (int vq = 0; vq < 4; ++vq) {
+      const int dh0 = mt * 32 + 8 * vq + 4 * lg;
+      if (dh0 < DH) {
+        uint2 pk;
+        pk.x = pack_bf16x2(o[mt][4 * vq] * inv, o[mt][4 * vq + 1] * inv);
+        pk.y = pack_bf16x2(o[mt][4 * vq + 2] * inv, o[mt][4 * vq + 3] * inv);
+        *reinterpret_cast<uint2*>(so + lr * KSTR + dh0 * 2) = pk;
       }
+    }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave reads back only what it wrote itself
+  for (int i = lane; i < 32 * KCH; i += 64) {
+    const int r = i / KCH, c = i - r * KCH;
+    if (wave * 32 + r < n) {
+      const uint4 v = *reinterpret_cast<const uint4*>(so + r * KSTR + c * 16);
+      *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.out) + (size_t)(w.q0 + wave * 32 + r) * a.ldo + head * DH + c * 8) = v;
+    }
   }
 }
 
@@ -155,7 +166,7 @@ __global__ __launch_bounds__(128) void attn_window_kernel(AttnArgs a) {
 // queries must already carry the softmax scale; the caller guarantees both.
 hipError_t launch_attn_window_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.n_work == 0 || a.heads == 0) return hipSuccess;
-  if (!a.prescaled || a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
+  if (!a.prescaled || a.ldqk % 8 || a.ldv % 8 || a.ldo % 8 || reinterpret_cast<uintptr_t>(a.out) % 16) return hipErrorInvalidValue;
   const int64_t total = (int64_t)a.n_work * a.heads;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
