@@ -75,10 +75,12 @@ int fail_hip(tcmv_ctx* ctx, hipError_t e, const char* what) {
 // Query rows per attention work item on the bf16 path.  Head sizes up to 80 allow two query
 // tiles per wave (256 rows with 4 waves, 512 with 8); 512-row items stage every K/V tile once per
 // CU instead of twice and are used when rounding the segments up to 512 rows wastes little.
-int attn_bq_bf16(int dh, const std::vector<int64_t>& seg_len) {
+int attn_bq_bf16(int dh, int heads, const std::vector<int64_t>& seg_len) {
   if (dh > 80) return 128;
-  int64_t rows = 0, padded = 0;
-  for (int64_t n : seg_len) { rows += n; padded += (n + 511) / 512 * 512; }
+  int64_t rows = 0, padded = 0, items256 = 0;
+  for (int64_t n : seg_len) { rows += n; padded += (n + 511) / 512 * 512; items256 += (n + 255) / 256; }
+  // a single small request: fewer 256-row work items than CUs; 128-row items double the workgroups
+  if (items256 * heads < 256) return 128;
   return (rows > 0 && padded * 100 <= rows * 103) ? 512 : 256;
 }
 
@@ -144,7 +146,7 @@ int64_t k_pad_of(const tcmv_model_desc& d) {
 
 size_t elt(const tcmv_ctx* c) { return c->desc.dtype == TCMV_BF16 ? 2 : 4; }
 
-struct EncodeWs { size_t xn, qkv, vt, h, kmax, kmax_bytes, total; };
+struct EncodeWs { size_t xn, qkv, vt, h, kmax, kmax_bytes, splitk, splitk_bytes, total; };
 EncodeWs encode_ws(const tcmv_plan* p) {
   const tcmv_model_desc& d = p->ctx->desc;
   const size_t e = elt(p->ctx);
@@ -165,6 +167,10 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   // (+ one word behind the table: "some workgroup needs the reference-tracking kernel")
   w.kmax_bytes = align_up(((size_t)std::max(p->n_segments, p->n_windows) * d.heads + 1) * 4, 256);
   w.kmax = off; off += d.dtype == TCMV_BF16 ? w.kmax_bytes : 0;
+  // one small request: room for the four k-slices of the fc2 product (see GemmArgs::partial)
+  const bool few_rows = d.dtype == TCMV_BF16 && ((T + 127) / 128) * (((size_t)d.d + 127) / 128) < 200;
+  w.splitk_bytes = few_rows ? align_up(4 * T * (size_t)d.d * sizeof(float), 256) : 0;
+  w.splitk = off; off += w.splitk_bytes;
   w.total = off;
   return w;
 }
@@ -487,7 +493,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
       return bad("too many tokens in one plan: tokens x widest activation row (max of 3d, mlp, merge^2 d, k_pad) must stay below 2^32");
   }
   p->n_segments = (int)seg_start.size();
-  p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), seg_len) : kAttnBQ_f32;
+  p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), d.heads, seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
   // The key-norm pass costs one read of K per layer; what it can save grows with the number of keys per query.
@@ -716,6 +722,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
       GemmArgs g{};
       g.a = hbuf; g.lda = d.mlp; g.w = L[10]; g.bias = f(11); g.c = x; g.ldc = d.d; g.m = T; g.n = d.d; g.k = d.mlp;
       g.epi = EPI_RESID;
+      if (ws.splitk_bytes) g.partial = reinterpret_cast<float*>(wsb + ws.splitk);
       TCMV_CHECK(timed(ctx, TCMV_K_FC2_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "fc2 GEMM");
     }
   }
@@ -812,7 +819,7 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   L.T = n_seg > 0 ? cu[n_seg] : 0;
   L.t_vpad = vp;
   std::vector<AttnWork> wtmp;
-  L.bq = dtype == TCMV_BF16 ? attn_bq_bf16(d / heads, sl) : kAttnBQ_f32;
+  L.bq = dtype == TCMV_BF16 ? attn_bq_bf16(d / heads, heads, sl) : kAttnBQ_f32;
   build_work(wtmp, ss, sl, sv, L.bq);
   if (vcol) {
     vcol->assign((size_t)L.T, 0);

@@ -45,10 +45,12 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
 
   const int tiles_n = (g.n + BN - 1) / BN;
   const int tiles_m = (int)((g.m + BM - 1) / BM);
-  const int total = tiles_m * tiles_n;
+  const int nslice = (EPI == EPI_PARTIAL) ? g.ksplit : 1;   // slices of k (neighbouring workgroups take the slices of a tile)
+  const int total = tiles_m * tiles_n * nslice;
   const int chunk = (total + 7) >> 3;
-  const int p = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
-  if (p >= total) return;
+  const int pq = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+  if (pq >= total) return;
+  const int p = pq / nslice, slice = pq - p * nslice;
   // tiles are walked in groups of GM rows of tiles, column by column inside a group: the
   // workgroups that run at the same time on one XCD then form a roughly square block of
   // tiles and share both A rows and W rows in that XCD's L2
@@ -92,11 +94,13 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
       offb[i] = (uint32_t)gn * (uint32_t)g.k + ((pc ^ ((row >> SW_SHIFT) & (CPR - 1))) << 3);
     }
   }
+  const int nk = g.k / BK / nslice;               // k-tiles of this workgroup
+  const int k_first = slice * nk;
   auto load_tiles = [&](int kt, int buf) {
     uint8_t* sa = smem + buf * STAGE;
     uint8_t* sb = sa + A_BYTES;
-    const uint16_t* ak = A + (size_t)kt * BK;
-    const uint16_t* wk = W + (size_t)kt * BK;
+    const uint16_t* ak = A + (size_t)(k_first + kt) * BK;
+    const uint16_t* wk = W + (size_t)(k_first + kt) * BK;
 #pragma unroll
     for (int i = 0; i < NLA; ++i)
       __builtin_amdgcn_global_load_lds((gptr_t)(ak + offa[i]), (lptr_t)(sa + (wave_u + WAVES * i) * 1024), 16, 0, 0);
@@ -116,7 +120,6 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
   // NSTAGE-deep ring of LDS stages: tile kt+NSTAGE-1 is requested while tile kt is
   // multiplied.  Loads of one wave complete in order, so "all but the newest
   // (NSTAGE-2) tiles have landed" is a vmcnt threshold of (NSTAGE-2)*(NLA+NLB).
-  const int nk = g.k / BK;
 #pragma unroll
   for (int st = 0; st < NSTAGE - 1; ++st)
     if (st < nk) load_tiles(st, st);
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
     const int c4 = (lane % LPR) * 4;
     const int col = wcol0 + nb * 32 + c4;
     float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (g.bias && col < g.n) b4 = *reinterpret_cast<const float4*>(g.bias + col);
+    if (EPI != EPI_PARTIAL && g.bias && col < g.n) b4 = *reinterpret_cast<const float4*>(g.bias + col);
 #pragma unroll
     for (int ps = 0; ps < 32 / RPP; ++ps) {
       const int r = ps * RPP + lane / LPR;
@@ -232,6 +235,8 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
         pk.x = pack_bf16x2(val.x, val.y);
         pk.y = pack_bf16x2(val.z, val.w);
         *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
+      } else if (EPI == EPI_PARTIAL) {
+        *reinterpret_cast<float4*>(g.partial + ((size_t)slice * g.m + row) * g.n + col) = val;
       } else if (EPI == EPI_RESID) {
         float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
         float4 old = *c;
@@ -292,7 +297,7 @@ template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, int MINB>
 static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
   const int tiles_n = (a.n + BN - 1) / BN;
   const int64_t tiles_m = (a.m + BM - 1) / BM;
-  const int64_t total = tiles_m * tiles_n;
+  const int64_t total = tiles_m * tiles_n * (a.epi == EPI_PARTIAL ? a.ksplit : 1);
   if (total <= 0) return hipSuccess;
   if (total > (1 << 30)) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
@@ -311,11 +316,31 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
   }
   switch (a.epi) {
     TCMV_GEMM_CASE(EPI_STORE) TCMV_GEMM_CASE(EPI_GELU) TCMV_GEMM_CASE(EPI_RESID)
-    TCMV_GEMM_CASE(EPI_EMBED) TCMV_GEMM_CASE(EPI_QKV) TCMV_GEMM_CASE(EPI_GATED)
+    TCMV_GEMM_CASE(EPI_EMBED) TCMV_GEMM_CASE(EPI_QKV) TCMV_GEMM_CASE(EPI_GATED) TCMV_GEMM_CASE(EPI_PARTIAL)
     default: return hipErrorInvalidValue;
   }
 #undef TCMV_GEMM_CASE
   return hipGetLastError();
+}
+
+// C += bias + slice 0 + slice 1 + ... (in this order), 16 bytes per lane
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(float* c, int64_t ldc, const float* partial, const float* bias,
+                                                            int64_t m, int n, int nslice) {
+  const int n4 = n >> 2;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= m * n4) return;
+  const int64_t row = i / n4;
+  const int col = (int)(i - row * n4) * 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (bias) acc = *reinterpret_cast<const float4*>(bias + col);
+  for (int sl = 0; sl < nslice; ++sl) {
+    const float4 v = *reinterpret_cast<const float4*>(partial + ((size_t)sl * m + row) * n + col);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  float4* dst = reinterpret_cast<float4*>(c + (size_t)row * ldc + col);
+  float4 old = *dst;
+  old.x += acc.x; old.y += acc.y; old.z += acc.z; old.w += acc.w;
+  *dst = old;
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
@@ -345,6 +370,19 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // a single small request: fewer than 200 tiles of 128x128 leave most CUs idle; 64x64 tiles
   // (2 waves) quadruple the number of workgroups
   const int64_t mid_tiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);
+  if (mid_tiles < 200 && a.epi == EPI_RESID && a.partial && a.k >= 2048 && (a.k / 64) % 4 == 0 && a.n % 4 == 0) {
+    // a long contraction over few rows (fc2 of one small request): 64x64 tiles would each walk all of k and
+    // re-read both operands from L2 twice as often; 128x128 tiles over a quarter of k each give as many
+    // workgroups with a quarter of the iterations.  The slices are added to C in a fixed order afterwards.
+    GemmArgs g = a;
+    g.epi = EPI_PARTIAL; g.ksplit = 4;
+    const hipError_t e = launch_cfg<128, 128, 2, 2, 64, 2, 2>(g, s);
+    if (e != hipSuccess) return e;
+    const int64_t n4 = (int64_t)a.m * (a.n / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<float*>(a.c), a.ldc, a.partial, a.bias, a.m, a.n, 4);
+    return hipGetLastError();
+  }
   if (mid_tiles < 200) return launch_cfg<64, 64, 1, 2, 64, 2, 4>(a, s);
   return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
 }

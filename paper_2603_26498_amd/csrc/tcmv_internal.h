@@ -38,7 +38,8 @@ enum Epilogue {
   EPI_RESID = 2,   // C(fp32) += acc + bias
   EPI_EMBED = 3,   // C(fp32)[dst_row[r]] = acc + bias + position term
   EPI_QKV = 4,     // columns < split: C ; columns >= split: transposed-V buffer
-  EPI_GATED = 5    // columns come in (gate, up) pairs: C[:, j] = silu(gate_j) * up_j   (C has n/2 columns)
+  EPI_GATED = 5,   // columns come in (gate, up) pairs: C[:, j] = silu(gate_j) * up_j   (C has n/2 columns)
+  EPI_PARTIAL = 6  // internal: raw fp32 sums of one slice of k into partial[slice][m][n] (see GemmArgs::partial)
 };
 
 struct GemmArgs {
@@ -57,6 +58,10 @@ struct GemmArgs {
   const float* rope; int rope_dh;
   // EPI_QKV: columns below qcols (the queries) are multiplied by qscale before rounding (0 columns = off)
   int qcols; float qscale;
+  // EPI_RESID with few rows and a long contraction (one small request): when `partial` is given (fp32,
+  // room for 4 * m * n values) the launcher may cut k into 4 slices computed by 4 times as many workgroups
+  // and add the slices to C in slice order in a second kernel (same result from run to run)
+  float* partial; int ksplit;
 };
 
 struct AttnArgs {

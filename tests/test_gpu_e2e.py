@@ -209,3 +209,29 @@ def test_windows_of_up_to_64_tokens_with_ragged_edges(dh):
         check_patches(wl, ref, patches)
         assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], 2e-2, 0.999, f"ragged windows dh={dh} hidden")
         assert_tokens_close(out.float().cpu().numpy(), ref["out"], 2e-2, 0.999, f"ragged windows dh={dh} out")
+
+
+def test_single_small_request_with_long_mlp_contraction():
+    """One small request through a model whose fc2 contraction is long (mlp 2048 over 320 rows of tokens): the
+    library computes that product in four slices of k and adds them in a fixed order.  Result within the usual
+    bar, identical from run to run, and equal to what the same request gets inside a large batch (where the
+    product is computed undivided) up to fp32 summation order."""
+    rng = np.random.default_rng(41)
+    desc = workloads.qwen_like_desc(layers=2, d=320, heads=4, mlp=2048, out_dim=192, max_grid=16)
+    item = workloads.Item(workloads.IMAGE, 1, 224, 140, 224, 140, workloads.random_frames(rng, 1, 224, 140))
+    wl = workloads.Workload("one_small_request", desc, [item], workloads.make_weights(desc, 4100, random_affine=True))
+    ref = oracle.run(wl)
+    enc, pl, patches, hidden, out = run_gpu(wl)
+    assert_tokens_close(hidden.cpu().numpy(), ref["hidden"], 2e-2, 0.999, "single request hidden")
+    assert_tokens_close(out.float().cpu().numpy(), ref["out"], 2e-2, 0.999, "single request out")
+    again = enc.encode(pl, patches)
+    torch.cuda.synchronize()
+    assert torch.equal(hidden, again)
+    # the same request as the first of a batch large enough for the undivided product
+    others = [workloads.Item(workloads.IMAGE, 1, 224, 224, 224, 224, workloads.random_frames(rng, 1, 224, 224))
+              for _ in range(40)]
+    plb = enc.plan([item] + others)
+    hb = enc.encode(plb, enc.preprocess(plb))
+    torch.cuda.synchronize()
+    n = hidden.shape[0]
+    assert_tokens_close(hb[:n].cpu().numpy(), hidden.cpu().numpy().astype(np.float64), 2e-3, 0.99999, "batch vs alone")
