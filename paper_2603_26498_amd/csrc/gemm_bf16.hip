@@ -12,11 +12,19 @@
 //
 // The MFMA is issued with W as the row operand and A as the column operand, so
 // the accumulator holds C^T: a lane owns ONE output row (token) and, per 32x32
-// tile, four groups of four consecutive output columns.  The epilogue therefore
-// works on 4-wide vectors: one 16-byte read-modify-write for the fp32 residual,
-// one 8-byte store for bf16 outputs, a float4 of bias / position values; and the
-// transposed-V store of the QKV projection has consecutive lanes on consecutive
-// tokens (64-byte segments).
+// tile, four groups of four consecutive output columns.  Written out like that a
+// store instruction would touch 32 rows; each wave therefore passes its sub-tile
+// through a private LDS buffer (32 rows at a time, in column groups of at most 256)
+// and comes back with lanes running along the row: bias / position adds, GELU,
+// the gated product, the rotary rotation, the fp32 residual read-modify-write and
+// the bf16 stores all work on 16 contiguous bytes per lane.  Only the transposed-V
+// columns of the QKV projection leave from registers (consecutive lanes =
+// consecutive tokens = the contiguous direction of that buffer).
+//
+// Tiles: 256x256 or 256x320 (8 waves, one workgroup per CU) for large products,
+// 128x128 (4 waves, two per CU), 64x64 (2 waves) for a single small request; a long
+// contraction over few rows that accumulates into the residual stream is cut into
+// four slices of k whose fp32 partial sums a second kernel adds in slice order.
 //
 // Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each walk
 // a contiguous range of tiles: neighbouring tiles share A rows or W rows in the
