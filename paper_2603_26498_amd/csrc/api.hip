@@ -46,8 +46,8 @@ struct tcmv_plan {
   int n_windows = 0;
   int64_t max_win_len = 0;          // longest window (tokens)
   std::vector<float> lut;             // [3][256]
-  std::vector<PreStrip> strips;       // preprocessing work of requests that are copied line by line
-  std::vector<int32_t> run_rows;      // patch rows of requests that are produced run by run
+  std::vector<PreStrip> strips;       // preprocessing work of the strip kernel (line segments copied or resampled into LDS)
+  std::vector<int32_t> run_rows;      // patch rows produced run by run (unaligned frames, other patch sizes, window order)
   int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
   int n_segments = 0;
   int bq = 0;                         // query rows per attention work item of the full-segment layers

@@ -16,8 +16,8 @@ struct ItemDev {
   int row0;                // first patch row of this request
 };
 
-// One unit of preprocessing work for requests that need no resampling: up to
-// kStripTokens horizontally adjacent patches of one patch line of one frame group.
+// One unit of preprocessing work of the strip kernel: up to kStripTokens horizontally
+// adjacent patches of one patch line of one frame group.
 struct PreStrip { int item, t, ph, pw0; };
 constexpr int kStripTokens = 16;
 
