@@ -125,54 +125,57 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-  // NSTAGE-deep ring of LDS stages: tile kt+NSTAGE-1 is requested while tile kt is
-  // multiplied.  Loads of one wave complete in order, so "all but the newest
-  // (NSTAGE-2) tiles have landed" is a vmcnt threshold of (NSTAGE-2)*(NLA+NLB).
-#pragma unroll
-  for (int st = 0; st < NSTAGE - 1; ++st)
-    if (st < nk) load_tiles(st, st);
+  // Two LDS stages.  The barrier of a k-tile sits before its LAST k-step, not before its first: by then every
+  // wave has read all of the tile's fragments into registers (so the tile's stage can be refilled with tile
+  // kt+2 right after the barrier) and tile kt+1, requested a tile earlier, has had three quarters of an
+  // iteration to land.  After the barrier a wave asks for the first fragments of tile kt+1 and then still has
+  // the MFMAs of the last k-step of tile kt to issue, so no wave sits behind a barrier with nothing to do while
+  // its fragments travel.
+  static_assert(NSTAGE == 2 && BK / 16 >= 2, "the k-loop is written for two stages");
   const int lr = lane & 31, lg = lane >> 5;
-  int buf = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    if (NSTAGE == 3 && kt + 1 < nk) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLA + NLB) : "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();       // tile kt visible to all waves; stage of tile kt-1 no longer read by anyone
-    if (kt + NSTAGE - 1 < nk) {
-      int nb = buf + NSTAGE - 1;
-      if (nb >= NSTAGE) nb -= NSTAGE;
-      load_tiles(kt + NSTAGE - 1, nb);
-    }
-    const uint8_t* sa = smem + buf * STAGE;
+  bf16x8 af[2][MI], bfr[2][NI];        // fragments double-buffered in registers
+  auto frags = [&](int stage, int kk, int b) {
+    const uint8_t* sa = smem + stage * STAGE;
     const uint8_t* sb = sa + A_BYTES;
-    // fragments double-buffered in registers: the LDS reads of k-step kk+1 are issued before the MFMAs of kk
-    bf16x8 af[2][MI], bfr[2][NI];
-    auto frags = [&](int kk, int b) {
-      const int ch = kk * 2 + lg;
+    const int ch = kk * 2 + lg;
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
-        const int row = wm * TM + mi * 32 + lr;
-        af[b][mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
-      }
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int row = wn * TN + ni * 32 + lr;
-        bfr[b][ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
-      }
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frags(kk + 1, (kk + 1) & 1);
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][ni], af[kk & 1][mi], acc[mi][ni], 0, 0, 0);
+    for (int mi = 0; mi < MI; ++mi) {
+      const int row = wm * TM + mi * 32 + lr;
+      af[b][mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
     }
-    if (++buf == NSTAGE) buf = 0;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int row = wn * TN + ni * 32 + lr;
+      bfr[b][ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> SW_SHIFT) & (CPR - 1))) << 4));
+    }
+  };
+  auto mfmas = [&](int b) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][ni], af[b][mi], acc[mi][ni], 0, 0, 0);
+  };
+  constexpr int KK = BK / 16;
+  load_tiles(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                     // tile 0 visible to all waves
+  if (1 < nk) load_tiles(1, 1);
+  frags(0, 0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+#pragma unroll
+    for (int kk = 0; kk + 1 < KK; ++kk) {
+      frags(cur, kk + 1, (kk + 1) & 1);
+      mfmas(kk & 1);
+    }
+    if (kt + 1 < nk) {
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // tile kt+1 has landed; this wave has all fragments of tile kt
+      __syncthreads();                 // ... and so has every other wave: tile kt+1 visible, stage of tile kt free
+      if (kt + 2 < nk) load_tiles(kt + 2, cur);
+      frags(cur ^ 1, 0, KK & 1);
+    }
+    mfmas((KK - 1) & 1);
   }
 
   // ---- epilogue.  In the accumulator a lane holds row (lane & 31) and columns
