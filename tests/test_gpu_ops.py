@@ -168,6 +168,31 @@ def test_attention(lens, d, heads, qs, dtype):
         assert np.sqrt(((got - ref) ** 2).mean()) <= 4e-3 * np.sqrt((ref ** 2).mean())
 
 
+@pytest.mark.parametrize("lens,qs,big_head", [
+    ([1000, 333, 1, 0, 640, 257, 129, 2048], 6.0, None),     # ragged: 256-row work items (4 waves x 2 query tiles), peaked
+    ([2048, 2048, 1024], 6.0, None),                          # multiples of 512: 512-row work items (8 waves), peaked
+    ([4096, 3072], 1.0, 3),                                   # long segments: key-norm bound holds except for one head
+])
+def test_attention_large_work_items(lens, qs, big_head):
+    """Enough work items for the kernels with two query tiles per wave to be chosen (a single small problem
+    gets 128-row items): 16 heads of 80, ragged and aligned segments, peaked scores (rescaling path), and long
+    segments on which the reference-free copy handles all heads but one."""
+    rng = np.random.default_rng(sum(lens))
+    d, heads, dh = 1280, 16, 80
+    cu = [0] + list(np.cumsum(lens))
+    T = cu[-1]
+    q = rng.normal(0, qs, (T, d)); k = rng.normal(0, 1, (T, d)); v = rng.normal(0, 1, (T, d))
+    if big_head is not None:
+        q[:, big_head * dh:(big_head + 1) * dh] *= 8.0
+    qkv = bf16_grid(np.concatenate([q, k, v], 1).astype(np.float32))
+    x = qkv.astype(np.float64)
+    ref = oe.attention(x[:, :d], x[:, d:2 * d], x[:, 2 * d:], cu, heads)
+    got = _attn("bf16", qkv, [int(c) for c in cu], d, heads)
+    assert np.abs(got - ref).max() <= 1.2e-2 * np.abs(ref).max()
+    assert_tokens_close(got, ref, 2e-2, 0.9995, "attention, large work items")
+    assert np.sqrt(((got - ref) ** 2).mean()) <= 4e-3 * np.sqrt((ref ** 2).mean())
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_attention_segments_do_not_leak(dtype):
     """Encode {A, B} together == A and B alone; huge values in B must not move A."""
