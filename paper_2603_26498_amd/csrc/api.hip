@@ -583,6 +583,7 @@ int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) 
   if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
   if (p->n_patch_rows == 0) return TCMV_OK;
   if (!d_patches) return fail(ctx, TCMV_E_INVALID_ARG, "null patch buffer");
+  if (reinterpret_cast<uintptr_t>(d_patches) % 16) return fail(ctx, TCMV_E_INVALID_ARG, "patch buffer must be 16-byte aligned");
   for (const ItemDev& it : p->items)
     if (it.n_frames > 0 && !it.frames) return fail(ctx, TCMV_E_INVALID_ARG, "an item with frames has a null frame pointer");
   int rc = ensure_uploaded(ctx, p);
