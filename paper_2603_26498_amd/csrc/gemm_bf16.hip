@@ -162,7 +162,9 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
   __syncthreads();                     // tile 0 visible to all waves
   if (1 < nk) load_tiles(1, 1);
   frags(0, 0, 0);
-  for (int kt = 0; kt < nk; ++kt) {
+  // mode 2: tile kt+2 exists and is requested; 1: tile kt+1 is the last; 0: tile kt is the last
+  auto iteration = [&](int kt, auto mode_c) {
+    constexpr int MODE = decltype(mode_c)::value;
     const int cur = kt & 1;
 #pragma unroll
     for (int kk = 0; kk + 1 < KK; ++kk) {
@@ -180,13 +182,29 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
         if (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0);
       }
     }
-    if (kt + 1 < nk) {
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // tile kt+1 has landed; this wave has all fragments of tile kt
-      __syncthreads();                 // ... and so has every other wave: tile kt+1 visible, stage of tile kt free
-      if (kt + 2 < nk) load_tiles(kt + 2, cur);
+    if (MODE >= 1) {
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (MODE == 2) load_tiles(kt + 2, cur);
       frags(cur ^ 1, 0, KK & 1);
     }
     mfmas((KK - 1) & 1);
+    if (MODE >= 1) {
+      // after the barrier: an MFMA first, then the tile loads and fragment reads one by one between the MFMAs
+      constexpr int NR = MI + NI, NM = MI * NI, NV = (MODE == 2) ? NLA + NLB : 0;
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    }
+  };
+  {
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) iteration(kt, std::integral_constant<int, 2>{});
+    if (kt + 1 < nk) { iteration(kt, std::integral_constant<int, 1>{}); ++kt; }
+    iteration(kt, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue.  In the accumulator a lane holds row (lane & 31) and columns
