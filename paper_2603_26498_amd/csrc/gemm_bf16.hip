@@ -4,31 +4,42 @@
 // the same way: direct global -> LDS loads (16 bytes per lane, no registers in
 // between) into tiles of 64 k-elements per row (128 bytes), with the 16-byte
 // chunk index XOR-swizzled by (row/2)%8 so that the per-lane 16-byte MFMA operand
-// reads are conflict-free: the LDS serves 16 lanes x 16 bytes per clock over 64
-// banks, two 128-byte rows span the banks, so 16 consecutive rows reading the
-// same logical chunk must land on 16 different 16-byte bank groups.  LDS is double buffered and
-// the next tile's loads are issued before the current tile's MFMAs.  Each wave owns a (BM/WM) x (BN/WN) sub-tile
-// built from v_mfma_f32_32x32x16_bf16.
+// reads are conflict-free.  LDS is double buffered and the next tile's loads are
+// issued before the current tile's MFMAs.  Each wave owns a (BM/WM) x (BN/WN)
+// sub-tile built from v_mfma_f32_32x32x16_bf16.
 //
 // The MFMA is issued with W as the row operand and A as the column operand, so
 // the accumulator holds C^T: a lane owns ONE output row (token) and, per 32x32
 // tile, four groups of four consecutive output columns.  Written out like that a
 // store instruction would touch 32 rows; each wave therefore passes its sub-tile
-// through a private LDS buffer (32 rows at a time, in column groups of at most 256)
-// and comes back with lanes running along the row: bias / position adds, GELU,
-// the gated product, the rotary rotation, the fp32 residual read-modify-write and
-// the bf16 stores all work on 16 contiguous bytes per lane.  Only the transposed-V
-// columns of the QKV projection leave from registers (consecutive lanes =
-// consecutive tokens = the contiguous direction of that buffer).
+// through a private LDS buffer (32 rows x 64 columns at a time) and comes back
+// with lanes running along the row, 8 consecutive columns per lane: bias /
+// position adds, GELU, the gated product, the rotary rotation, the fp32 residual
+// read-modify-write and the stores all work on 16 or 32 contiguous bytes per
+// lane.  All reads of a group (staged sums, old residual values) are issued
+// before the first result is computed, so their round trips overlap instead of
+// queueing behind each other.  Only the transposed-V columns of the QKV
+// projection leave from registers (consecutive lanes = consecutive tokens = the
+// contiguous direction of that buffer).
 //
-// Tiles: 256x256 or 256x320 (8 waves, one workgroup per CU) for large products,
-// 128x128 (4 waves, two per CU), 64x64 (2 waves) for a single small request; a long
-// contraction over few rows that accumulates into the residual stream is cut into
-// four slices of k whose fp32 partial sums a second kernel adds in slice order.
+// Large products run on a PERSISTENT kernel: one workgroup of 8 waves per CU walks
+// a list of 256x320 (or 256x256) tiles.  While it finishes the k-loop of one tile
+// it already requests the first k-tile of its next tile, the tile is written out
+// from the stage that is free by then, and the stores drain while the next
+// k-loop runs.  Operands are read through buffer descriptors (base and size in
+// SGPRs, one 32-bit lane offset per operand, everything else in the scalar
+// offset), and the last tile of a dimension is shifted back to end at the matrix
+// edge so that no load ever leaves the operand (its repeated rows / columns are
+// skipped when it is written out).
+// Smaller products use one workgroup per tile: 128x128 (4 waves, two per CU),
+// 64x64 (2 waves) for a single small request; a long contraction over few rows
+// that accumulates into the residual stream is cut into four slices of k whose
+// fp32 partial sums a second kernel adds in slice order.
 //
 // Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each walk
 // a contiguous range of tiles: neighbouring tiles share A rows or W rows in the
 // XCD's own L2.
+#include <algorithm>
 #include <type_traits>
 #include "tcmv_internal.h"
 #include "device_utils.h"
@@ -38,7 +49,163 @@ namespace tcmv {
 namespace {
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+constexpr int kEpStride = 68;                      // floats per row of a wave's staging buffer (64 columns + 4: conflict-free)
+constexpr int kEpWaveBytes = 32 * kEpStride * 4;   // staging bytes per wave
 }  // namespace
+
+// Rows and columns of the output that a workgroup may write: [row_lo, row_hi) x [col_lo, col_hi).
+struct TileBounds { int64_t row_lo, row_hi; int col_lo, col_hi; int slice; };
+
+// Writes one wave's sub-tile (MI x NI accumulator tiles of 32 x 32, first row m_base, first column wcol0).  In the
+// accumulator a lane holds row (lane & 31) and columns 8*(v/4) + 4*(lane>>5) + v%4 of each tile.  The sub-tile
+// leaves through the wave's private LDS buffer `ep` (32 rows x 64 columns of fp32 at a time) and comes back with
+// lanes running along the rows, 8 consecutive columns per lane.  FULL: every element is inside the bounds.
+template <int EPI, int MI, int NI, bool FULL>
+__device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmArgs& g, float* ep, int64_t m_base, int wcol0,
+                                              int lane, const TileBounds& tb) {
+  constexpr int EPS = kEpStride;
+  constexpr int TN = NI * 32;
+  const int lr = lane & 31, lg = lane >> 5;
+  auto flush = [&](auto ngc, int mi, int nb, int64_t rbase) {
+    constexpr int NGT = decltype(ngc)::value;
+    constexpr int LPR = NGT * 4;                   // lanes per row (8 columns each)
+    constexpr int RPP = 64 / LPR;                  // rows per pass
+    constexpr int NP = 32 / RPP;                   // passes
+    const int c8 = (lane % LPR) * 8;
+    const int col = wcol0 + nb * 32 + c8;
+    const int r0 = lane / LPR;
+    const bool col_ok = FULL || (col >= tb.col_lo && col < tb.col_hi);
+    float4 o[NP][2];
+    if (EPI == EPI_RESID) {
+#pragma unroll
+      for (int ps = 0; ps < NP; ++ps) {
+        const int64_t row = rbase + ps * RPP + r0;
+        if (FULL || (row >= tb.row_lo && row < tb.row_hi && col_ok)) {
+          const float4* c = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.c) + (size_t)row * g.ldc + col);
+          o[ps][0] = c[0]; o[ps][1] = c[1];
+        }
+      }
+    }
+#pragma unroll
+    for (int ni = 0; ni < NGT; ++ni)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq)
+        *reinterpret_cast<float4*>(ep + lr * EPS + ni * 32 + 8 * vq + 4 * lg) =
+            make_float4(acc[mi][nb + ni][4 * vq], acc[mi][nb + ni][4 * vq + 1], acc[mi][nb + ni][4 * vq + 2], acc[mi][nb + ni][4 * vq + 3]);
+    float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
+    if (EPI != EPI_PARTIAL && g.bias && col_ok) { b0 = *reinterpret_cast<const float4*>(g.bias + col); b1 = *reinterpret_cast<const float4*>(g.bias + col + 4); }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    float4 v[NP][2];
+    if (EPI != EPI_RESID) {
+#pragma unroll
+      for (int ps = 0; ps < NP; ++ps) {
+        const int r = ps * RPP + r0;
+        v[ps][0] = *reinterpret_cast<const float4*>(ep + r * EPS + c8);
+        v[ps][1] = *reinterpret_cast<const float4*>(ep + r * EPS + c8 + 4);
+      }
+    }
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) {
+      const int64_t row = rbase + ps * RPP + r0;
+      if (!FULL && (row < tb.row_lo || row >= tb.row_hi || !col_ok)) continue;
+      if (EPI == EPI_RESID) {                       // the old values hold the registers; read the staged sums pass by pass
+        const int r = ps * RPP + r0;
+        v[ps][0] = *reinterpret_cast<const float4*>(ep + r * EPS + c8);
+        v[ps][1] = *reinterpret_cast<const float4*>(ep + r * EPS + c8 + 4);
+      }
+      float x[8] = {v[ps][0].x + b0.x, v[ps][0].y + b0.y, v[ps][0].z + b0.z, v[ps][0].w + b0.w,
+                    v[ps][1].x + b1.x, v[ps][1].y + b1.y, v[ps][1].z + b1.z, v[ps][1].w + b1.w};
+      if (EPI == EPI_GATED) {
+        uint2 pk;
+        float h[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) h[j] = x[2 * j] / (1.0f + __expf(-x[2 * j])) * x[2 * j + 1];
+        pk.x = pack_bf16x2(h[0], h[1]); pk.y = pack_bf16x2(h[2], h[3]);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + (col >> 1)) = pk;
+      } else if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
+        if (EPI == EPI_QKV && col >= g.split) continue;
+        if (EPI == EPI_QKV && col < g.qcols) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] *= g.qscale;
+        }
+        if (EPI == EPI_QKV && g.rope) {
+          const int p2 = ((col % g.rope_dh) >> 1) * 2;
+          const float4* cs = reinterpret_cast<const float4*>(g.rope + (size_t)row * g.rope_dh + p2);
+          const float4 c0 = cs[0], c1 = cs[1];
+          const float a0 = x[0], a1 = x[1], a2 = x[2], a3 = x[3], a4 = x[4], a5 = x[5], a6 = x[6], a7 = x[7];
+          x[0] = a0 * c0.x - a1 * c0.y; x[1] = a0 * c0.y + a1 * c0.x;
+          x[2] = a2 * c0.z - a3 * c0.w; x[3] = a2 * c0.w + a3 * c0.z;
+          x[4] = a4 * c1.x - a5 * c1.y; x[5] = a4 * c1.y + a5 * c1.x;
+          x[6] = a6 * c1.z - a7 * c1.w; x[7] = a6 * c1.w + a7 * c1.z;
+        }
+        if (EPI == EPI_GELU) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = gelu_bf16(x[j]);
+        }
+        uint4 pk;
+        pk.x = pack_bf16x2(x[0], x[1]); pk.y = pack_bf16x2(x[2], x[3]); pk.z = pack_bf16x2(x[4], x[5]); pk.w = pack_bf16x2(x[6], x[7]);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
+      } else if (EPI == EPI_PARTIAL) {
+        float4* c = reinterpret_cast<float4*>(g.partial + ((size_t)tb.slice * g.m + row) * g.n + col);
+        c[0] = make_float4(x[0], x[1], x[2], x[3]);
+        c[1] = make_float4(x[4], x[5], x[6], x[7]);
+      } else if (EPI == EPI_RESID) {
+        float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
+        c[0] = make_float4(o[ps][0].x + x[0], o[ps][0].y + x[1], o[ps][0].z + x[2], o[ps][0].w + x[3]);
+        c[1] = make_float4(o[ps][1].x + x[4], o[ps][1].y + x[5], o[ps][1].z + x[6], o[ps][1].w + x[7]);
+      } else if (EPI == EPI_EMBED) {
+        const int pi = g.pos_idx ? g.pos_idx[row] : 0;
+        if (g.pos_kind == 1) {
+          const float4* p0 = reinterpret_cast<const float4*>(g.pos0 + (size_t)pi * g.n + col);
+          const float4 pa = p0[0], pb = p0[1];
+          x[0] += pa.x; x[1] += pa.y; x[2] += pa.z; x[3] += pa.w; x[4] += pb.x; x[5] += pb.y; x[6] += pb.z; x[7] += pb.w;
+        } else if (g.pos_kind == 2) {
+          const float4* p0 = reinterpret_cast<const float4*>(g.pos0 + (size_t)(pi & 0xFFFF) * g.n + col);
+          const float4* p1 = reinterpret_cast<const float4*>(g.pos1 + (size_t)(pi >> 16) * g.n + col);
+          const float4 pa = p0[0], pb = p0[1], qa = p1[0], qb = p1[1];
+          x[0] += pa.x + qa.x; x[1] += pa.y + qa.y; x[2] += pa.z + qa.z; x[3] += pa.w + qa.w;
+          x[4] += pb.x + qb.x; x[5] += pb.y + qb.y; x[6] += pb.z + qb.z; x[7] += pb.w + qb.w;
+        }
+        const int64_t dst = g.dst_row ? (int64_t)g.dst_row[row] : row;
+        float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col);
+        c[0] = make_float4(x[0], x[1], x[2], x[3]);
+        c[1] = make_float4(x[4], x[5], x[6], x[7]);
+      }
+    }
+    asm volatile("" ::: "memory");
+  };
+
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int64_t rbase = m_base + mi * 32;
+    if (EPI == EPI_QKV && wcol0 + TN > g.split) {
+      const int64_t row = rbase + lr;
+      if (FULL || (row >= tb.row_lo && row < tb.row_hi)) {
+        const int vc = g.vcol[row];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int col = wcol0 + ni * 32 + 8 * vq + 4 * lg;
+            if (col >= g.split && (FULL || (col >= tb.col_lo && col < tb.col_hi))) {
+              float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+              if (g.bias) b4 = *reinterpret_cast<const float4*>(g.bias + col);
+              uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
+              vt[0] = f32_to_bf16(acc[mi][ni][4 * vq] + b4.x);
+              vt[g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 1] + b4.y);
+              vt[2 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 2] + b4.z);
+              vt[3 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 3] + b4.w);
+            }
+          }
+      }
+      if (wcol0 >= g.split) continue;
+    }
+#pragma unroll
+    for (int nb = 0; nb + 2 <= NI; nb += 2) flush(std::integral_constant<int, 2>{}, mi, nb, rbase);
+    if (NI & 1) flush(std::integral_constant<int, 1>{}, mi, NI - 1, rbase);
+  }
+}
+
 
 template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, int MINB, int EPI>
 __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g) {
@@ -207,129 +374,16 @@ __global__ __launch_bounds__(WM* WN * 64, MINB) void gemm_bf16_kernel(GemmArgs g
     iteration(kt, std::integral_constant<int, 0>{});
   }
 
-  // ---- epilogue.  In the accumulator a lane holds row (lane & 31) and columns
-  // 8*(v/4) + 4*(lane>>5) + v%4 of each 32x32 tile: writing that to a row-major matrix
-  // directly would touch 32 cache lines per store instruction.  Each wave therefore
-  // passes its sub-tile through a private LDS buffer, 32 rows at a time, and comes
-  // back with lanes running along the row (16 bytes per lane): stores and the fp32
-  // residual read-modify-write are full contiguous segments.  Only the transposed-V
-  // part of the QKV projection keeps the register layout (there consecutive lanes =
-  // consecutive tokens is exactly the contiguous direction).
-  // A wave tile whose width divides 256 columns goes through the buffer in one piece; any
-  // other width (160 columns of the 256x320 tile) in groups of two 32-column tiles, the odd
-  // one last.
-  constexpr int GN = (256 % TN == 0) ? NI : 2;     // 32-column tiles per group
-  constexpr int EPS = GN * 32 + 4;                 // padded row stride of the staging buffer (floats)
-  static_assert(WAVES * 32 * EPS * 4 <= NSTAGE * STAGE, "epilogue staging does not fit in the operand stages");
-  static_assert(TN % 32 == 0, "wave tile width");
-  __syncthreads();                                 // every wave is done with the operand stages
-  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPS);
-  const int wcol0 = n0 + wn * TN;
-
-  // one group of NGT tiles (columns nb*32 .. nb*32 + NGT*32 of the wave tile) of 32 rows: registers -> LDS -> global
-  auto flush = [&](auto ngc, int mi, int nb, int64_t rbase) {
-    constexpr int NGT = decltype(ngc)::value;
-    constexpr int LPR = NGT * 8;                   // lanes per row when reading back
-    constexpr int RPP = 64 / LPR;                  // rows per read pass
-    // registers -> LDS (lane = row)
-#pragma unroll
-    for (int ni = 0; ni < NGT; ++ni)
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq)
-        *reinterpret_cast<float4*>(ep + lr * EPS + ni * 32 + 8 * vq + 4 * lg) =
-            make_float4(acc[mi][nb + ni][4 * vq], acc[mi][nb + ni][4 * vq + 1], acc[mi][nb + ni][4 * vq + 2],
-                        acc[mi][nb + ni][4 * vq + 3]);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same-wave LDS ops complete in order; keep the compiler from reordering
-    // LDS -> global (lanes along the row)
-    const int c4 = (lane % LPR) * 4;
-    const int col = wcol0 + nb * 32 + c4;
-    float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (EPI != EPI_PARTIAL && g.bias && col < g.n) b4 = *reinterpret_cast<const float4*>(g.bias + col);
-#pragma unroll
-    for (int ps = 0; ps < 32 / RPP; ++ps) {
-      const int r = ps * RPP + lane / LPR;
-      const int64_t row = rbase + r;
-      float4 val = *reinterpret_cast<const float4*>(ep + r * EPS + c4);
-      if (row >= g.m || col >= g.n) continue;
-      val.x += b4.x; val.y += b4.y; val.z += b4.z; val.w += b4.w;
-      if (EPI == EPI_GATED) {
-        // columns (col, col+1) and (col+2, col+3) are (gate, up) pairs of output columns col/2 and col/2 + 1
-        const float h0 = val.x / (1.0f + __expf(-val.x)) * val.y;
-        const float h1 = val.z / (1.0f + __expf(-val.z)) * val.w;
-        *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + (col >> 1)) = pack_bf16x2(h0, h1);
-      } else if (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_QKV) {
-        if (EPI == EPI_QKV && col >= g.split) continue;
-        if (EPI == EPI_QKV && col < g.qcols) { val.x *= g.qscale; val.y *= g.qscale; val.z *= g.qscale; val.w *= g.qscale; }
-        if (EPI == EPI_QKV && g.rope) {
-          // rotary positions: the lane holds element pairs p and p+1 of one head (col % 4 == 0, head size % 4 == 0)
-          const int p2 = ((col % g.rope_dh) >> 1) * 2;
-          const float4 cs = *reinterpret_cast<const float4*>(g.rope + (size_t)row * g.rope_dh + p2);   // cos, sin, cos, sin
-          const float x0 = val.x, x1 = val.y, x2 = val.z, x3 = val.w;
-          val.x = x0 * cs.x - x1 * cs.y; val.y = x0 * cs.y + x1 * cs.x;
-          val.z = x2 * cs.z - x3 * cs.w; val.w = x2 * cs.w + x3 * cs.z;
-        }
-        if (EPI == EPI_GELU) {
-          val.x = gelu_fast(val.x); val.y = gelu_fast(val.y); val.z = gelu_fast(val.z); val.w = gelu_fast(val.w);
-        }
-        uint2 pk;
-        pk.x = pack_bf16x2(val.x, val.y);
-        pk.y = pack_bf16x2(val.z, val.w);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + (size_t)row * g.ldc + col) = pk;
-      } else if (EPI == EPI_PARTIAL) {
-        *reinterpret_cast<float4*>(g.partial + ((size_t)slice * g.m + row) * g.n + col) = val;
-      } else if (EPI == EPI_RESID) {
-        float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)row * g.ldc + col);
-        float4 old = *c;
-        old.x += val.x; old.y += val.y; old.z += val.z; old.w += val.w;
-        *c = old;
-      } else if (EPI == EPI_EMBED) {
-        const int pi = g.pos_idx ? g.pos_idx[row] : 0;
-        if (g.pos_kind == 1) {
-          const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)pi * g.n + col);
-          val.x += p0.x; val.y += p0.y; val.z += p0.z; val.w += p0.w;
-        } else if (g.pos_kind == 2) {
-          const float4 p0 = *reinterpret_cast<const float4*>(g.pos0 + (size_t)(pi & 0xFFFF) * g.n + col);
-          const float4 p1 = *reinterpret_cast<const float4*>(g.pos1 + (size_t)(pi >> 16) * g.n + col);
-          val.x += p0.x + p1.x; val.y += p0.y + p1.y; val.z += p0.z + p1.z; val.w += p0.w + p1.w;
-        }
-        const int64_t dst = g.dst_row ? (int64_t)g.dst_row[row] : row;
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.c) + (size_t)dst * g.ldc + col) = val;
-      }
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next group overwrites the buffer
-  };
-
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int64_t rbase = m0 + wm * TM + mi * 32;
-    if (EPI == EPI_QKV && wcol0 + TN > g.split) {
-      // transposed-V columns straight from registers
-      const int64_t row = rbase + lr;
-      if (row < g.m) {
-        const int vc = g.vcol[row];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-          for (int vq = 0; vq < 4; ++vq) {
-            const int col = wcol0 + ni * 32 + 8 * vq + 4 * lg;
-            if (col >= g.split && col < g.n) {
-              float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
-              if (g.bias) b4 = *reinterpret_cast<const float4*>(g.bias + col);
-              uint16_t* vt = reinterpret_cast<uint16_t*>(g.vt) + (size_t)(col - g.split) * g.ldvt + vc;
-              vt[0] = f32_to_bf16(acc[mi][ni][4 * vq] + b4.x);
-              vt[g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 1] + b4.y);
-              vt[2 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 2] + b4.z);
-              vt[3 * g.ldvt] = f32_to_bf16(acc[mi][ni][4 * vq + 3] + b4.w);
-            }
-          }
-      }
-      if (wcol0 >= g.split) continue;              // nothing else in this wave tile
-    }
-#pragma unroll
-    for (int nb = 0; nb < NI; nb += GN) {
-      if (nb + GN <= NI) flush(std::integral_constant<int, GN>{}, mi, nb, rbase);
-      else flush(std::integral_constant<int, 1>{}, mi, nb, rbase);
-    }
+  // ---- epilogue: through the operand stages, which every wave has finished with
+  static_assert(WAVES * kEpWaveBytes <= NSTAGE * STAGE, "epilogue staging does not fit in the operand stages");
+  __syncthreads();
+  {
+    float* ep = reinterpret_cast<float*>(smem + wave * kEpWaveBytes);
+    const TileBounds tb{0, g.m, 0, g.n, slice};
+    const int64_t m_base = m0 + wm * TM;
+    const int wcol0 = n0 + wn * TN;
+    if (m0 + BM <= g.m && n0 + BN <= g.n) wave_epilogue<EPI, MI, NI, true>(acc, g, ep, m_base, wcol0, lane, tb);
+    else wave_epilogue<EPI, MI, NI, false>(acc, g, ep, m_base, wcol0, lane, tb);
   }
 }
 
@@ -383,34 +437,265 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(float* c, int64_t ld
   *dst = old;
 }
 
+// One wave-wide 16-byte-per-lane load global -> LDS through a buffer descriptor over `bytes` bytes at `base` (base,
+// size and `soff` are wave-uniform and live in SGPRs; `voff` is the lane's byte offset).  Lane l writes 16 bytes
+// at lds + 16 l.
+__device__ __forceinline__ void buffer_load_lds16(const void* base, uint32_t bytes, void* lds, uint32_t voff, uint32_t soff) {
+  const uint64_t v = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                                                      (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)lds, 16, voff, soff, 0, 0);
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM* WN * 64, 1) void gemm_bf16_persist_kernel(GemmArgs g) {
+  constexpr int BK = 64, TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  constexpr int ROWB = BK * 2, CPR = 8, RPL = 8, WAVES = WM * WN, KK = BK / 16;
+  constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+  constexpr int EP_WAVE = kEpWaveBytes, EP_BYTES = WAVES * EP_WAVE;
+  constexpr int EXTRA = EP_BYTES > STAGE ? (EP_BYTES - STAGE + 255) / 256 * 256 : 0;
+  constexpr int NLA = BM / RPL / WAVES, NLB = BN / RPL / WAVES;
+  static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "tile/waves mismatch");
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];      // [stage 0][extra][stage 1]
+
+  const int tiles_n = (g.n + BN - 1) / BN;
+  const int tiles_m = (int)((g.m + BM - 1) / BM);
+  const int total = tiles_m * tiles_n;
+  const int chunk = (total + 7) >> 3;
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslot = (int)(gridDim.x >> 3);
+  int pq = xcd * chunk + slot;
+  const int pq_end = min((xcd + 1) * chunk, total);
+  if (pq >= pq_end) return;
+  constexpr int GM = 8;
+  auto tile_of = [&](int p, int& tm, int& tn) {
+    const int per_group = GM * tiles_n;
+    const int grp = p / per_group, within = p - grp * per_group;
+    const int gm_eff = min(GM, tiles_m - grp * GM);
+    tn = within / gm_eff;
+    tm = grp * GM + (within - tn * gm_eff);
+  };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave_u / WN, wn = wave_u % WN;
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(g.a);
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(g.w);
+  const int nk = g.k / BK;
+
+  // sizes of the operands in bytes (below 2^32: checked by the launcher)
+  const uint32_t bytes_a = (uint32_t)(((uint64_t)(g.m - 1) * (uint64_t)g.lda + (uint64_t)g.k) * 2ull);
+  const uint32_t bytes_w = (uint32_t)((uint64_t)g.n * (uint64_t)g.k * 2ull);
+  // Tile loads: lane l of a wave-wide load fetches 16 bytes of row l/8 of an 8-row slab; the slab's first row, the
+  // k offset and the slab index go into the scalar offset of the instruction, so one VGPR per operand is enough.
+  // The last tile of a dimension is shifted back to end at the matrix edge (its first rows / columns then repeat
+  // the previous tile's and are skipped when the tile is written out), so every load stays inside the operand.
+  const int rl = lane / CPR, pc = lane % CPR;
+  const int swz = ((rl >> 1) + 4 * (wave_u & 1)) & 7;            // (row >> 1) & 7 for row = (wave + 8 i) * 8 + rl
+  const uint32_t lane_a = (uint32_t)rl * (uint32_t)g.lda * 2u + ((pc ^ swz) << 4);
+  const uint32_t lane_w = (uint32_t)rl * (uint32_t)g.k * 2u + ((pc ^ swz) << 4);
+  uint32_t tile_a = 0, tile_w = 0;                               // byte offset of the tile's first row (scalars)
+  int row_lo = 0, col_lo = 0;                                    // first row / column this tile owns
+  int64_t m0 = 0; int n0 = 0;
+  auto set_tile = [&](int tm_, int tn_) {
+    row_lo = tm_ * BM; col_lo = tn_ * BN;
+    m0 = min((int64_t)row_lo, g.m - BM); n0 = min(col_lo, g.n - BN);
+    tile_a = (uint32_t)(m0 * g.lda) * 2u;
+    tile_w = (uint32_t)n0 * (uint32_t)g.k * 2u;
+  };
+  auto stage_ptr = [&](int s) { return smem + (s ? STAGE + EXTRA : 0); };
+  auto load_tiles = [&](int kt, int s, uint32_t ta, uint32_t tw) {
+    uint8_t* sa = stage_ptr(s);
+    uint8_t* sb = sa + A_BYTES;
+    const uint32_t koff = (uint32_t)kt * (BK * 2);
+    const uint32_t slab_a = (uint32_t)(8 * g.lda * 2), slab_w = (uint32_t)(8 * g.k * 2);
+#pragma unroll
+    for (int i = 0; i < NLA; ++i)
+      buffer_load_lds16(A, bytes_a, sa + (wave_u + WAVES * i) * 1024, lane_a, ta + koff + (uint32_t)(wave_u + WAVES * i) * slab_a);
+#pragma unroll
+    for (int i = 0; i < NLB; ++i)
+      buffer_load_lds16(W, bytes_w, sb + (wave_u + WAVES * i) * 1024, lane_w, tw + koff + (uint32_t)(wave_u + WAVES * i) * slab_w);
+  };
+
+  f32x16 acc[MI][NI];
+  const int lr = lane & 31, lg = lane >> 5;
+  bf16x8 af[2][MI], bfr[2][NI];
+  auto frags = [&](int s, int kk, int b) {
+    const uint8_t* sa = stage_ptr(s);
+    const uint8_t* sb = sa + A_BYTES;
+    const int ch = kk * 2 + lg;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int row = wm * TM + mi * 32 + lr;
+      af[b][mi] = *reinterpret_cast<const bf16x8*>(sa + row * ROWB + ((ch ^ ((row >> 1) & 7)) << 4));
+    }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int row = wn * TN + ni * 32 + lr;
+      bfr[b][ni] = *reinterpret_cast<const bf16x8*>(sb + row * ROWB + ((ch ^ ((row >> 1) & 7)) << 4));
+    }
+  };
+  auto mfmas = [&](int b) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][ni], af[b][mi], acc[mi][ni], 0, 0, 0);
+  };
+
+  {
+    int tm, tn;
+    tile_of(pq, tm, tn);
+    set_tile(tm, tn);
+  }
+  int base = 0;                                  // stage of k-tile kt of the current tile = (kt + base) & 1
+  load_tiles(0, 0, tile_a, tile_w);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (nk > 1) load_tiles(1, 1, tile_a, tile_w);
+  frags(0, 0, 0);
+
+  // MODE 2: after the barrier request k-tile kt+2 of this tile; 3: request k-tile 0 of the next tile (if there is one);
+  // 0: last k-tile, nothing after it
+  auto iteration = [&](int kt, auto mode_c, int np, bool has_next) {
+    constexpr int MODE = decltype(mode_c)::value;
+    const int cur = (kt + base) & 1;
+#pragma unroll
+    for (int kk = 0; kk + 1 < KK; ++kk) {
+      frags(cur, kk + 1, (kk + 1) & 1);
+      mfmas(kk & 1);
+      {
+        constexpr int NR = MI + NI, NM = MI * NI;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+          if (i < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0);
+      }
+    }
+    if (MODE >= 2) {
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (MODE == 2) load_tiles(kt + 2, cur, tile_a, tile_w);
+      if (MODE == 3 && has_next) {
+        int tm2, tn2;
+        tile_of(np, tm2, tn2);
+        const int64_t m2 = min((int64_t)tm2 * BM, g.m - BM);
+        const int n2 = min(tn2 * BN, g.n - BN);
+        load_tiles(0, cur, (uint32_t)(m2 * g.lda) * 2u, (uint32_t)n2 * (uint32_t)g.k * 2u);
+      }
+      frags(cur ^ 1, 0, KK & 1);
+    }
+    mfmas((KK - 1) & 1);
+    if (MODE == 2) {
+      constexpr int NR = MI + NI, NM = MI * NI, NV = NLA + NLB;
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    }
+  };
+
+  for (;;) {
+    const int np = pq + nslot;
+    const bool has_next = np < pq_end;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    {
+      int kt = 0;
+      for (; kt + 2 < nk; ++kt) iteration(kt, std::integral_constant<int, 2>{}, np, has_next);
+      if (kt + 1 < nk) { iteration(kt, std::integral_constant<int, 3>{}, np, has_next); ++kt; }
+      iteration(kt, std::integral_constant<int, 0>{}, np, has_next);
+    }
+    const int s_last = (nk - 1 + base) & 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                               // every wave is done with the last stage; the next tile's first k-tile has landed
+    {
+      float* ep = reinterpret_cast<float*>(smem + (s_last ? STAGE : 0) + wave_u * EP_WAVE);
+      const int64_t m_base = m0 + wm * TM;
+      const int wcol0 = n0 + wn * TN;
+      const TileBounds tb{row_lo, g.m, col_lo, g.n, 0};
+      if (m0 == row_lo && n0 == col_lo) wave_epilogue<EPI, MI, NI, true>(acc, g, ep, m_base, wcol0, lane, tb);
+      else wave_epilogue<EPI, MI, NI, false>(acc, g, ep, m_base, wcol0, lane, tb);
+    }
+    if (!has_next) break;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();                               // the staging area is free again
+    pq = np;
+    {
+      int tm, tn;
+      tile_of(pq, tm, tn);
+      set_tile(tm, tn);
+    }
+    base = (base + nk) & 1;
+    if (nk > 1) load_tiles(1, (1 + base) & 1, tile_a, tile_w);
+    frags(base & 1, 0, 0);
+  }
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t launch_persist(const GemmArgs& a, hipStream_t s) {
+  const int tiles_n = (a.n + BN - 1) / BN;
+  const int64_t tiles_m = (a.m + BM - 1) / BM;
+  const int64_t total = tiles_m * tiles_n;
+  if (total <= 0) return hipSuccess;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  constexpr int STAGE = (BM + BN) * 128, EP_BYTES = WM * WN * kEpWaveBytes;
+  constexpr int EXTRA = EP_BYTES > STAGE ? (EP_BYTES - STAGE + 255) / 256 * 256 : 0;
+  const size_t lds = 2 * STAGE + EXTRA;
+  const unsigned grid = (unsigned)std::min<int64_t>(256, (total + 7) / 8 * 8);
+  dim3 block(WM * WN * 64);
+#define TCMV_PGEMM_CASE(E)                                                                             \
+  case E: {                                                                                            \
+    auto kern = gemm_bf16_persist_kernel<BM, BN, WM, WN, E>;                                           \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+    if (e != hipSuccess) return e;                                                                     \
+    hipLaunchKernelGGL(kern, dim3(grid), block, lds, s, a);                                            \
+    break;                                                                                             \
+  }
+  switch (a.epi) {
+    TCMV_PGEMM_CASE(EPI_STORE) TCMV_PGEMM_CASE(EPI_GELU) TCMV_PGEMM_CASE(EPI_RESID)
+    TCMV_PGEMM_CASE(EPI_EMBED) TCMV_PGEMM_CASE(EPI_QKV) TCMV_PGEMM_CASE(EPI_GATED)
+    default: return hipErrorInvalidValue;
+  }
+#undef TCMV_PGEMM_CASE
+  return hipGetLastError();
+}
+
+
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   if (a.m == 0 || a.n == 0) return hipSuccess;
   if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return hipErrorInvalidValue;
-  if (a.epi == EPI_QKV && (a.split % 4)) return hipErrorInvalidValue;
-  if (a.epi == EPI_QKV && a.rope && (a.rope_dh % 4 || a.rope_dh <= 0)) return hipErrorInvalidValue;
-  if (a.epi == EPI_GATED && (a.ldc % 2)) return hipErrorInvalidValue;
+  if (a.epi == EPI_QKV && (a.split % 8)) return hipErrorInvalidValue;
+  if (a.epi == EPI_QKV && a.rope && (a.rope_dh % 8 || a.rope_dh <= 0)) return hipErrorInvalidValue;
+  if (a.epi == EPI_GATED && (a.ldc % 4)) return hipErrorInvalidValue;
   // operand element offsets are kept in 32 bits
   if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return hipErrorInvalidValue;
-  // 256x256 tiles (8 waves, one workgroup per CU) when there are at least two full rounds of
-  // them and the output is wide or the contraction long, or at least four rounds whatever the
-  // shape; 128x128 tiles (4 waves, two workgroups per CU) otherwise.  (Measured on the
-  // encoder's shapes.)
+  // Persistent 256-row tiles (8 waves, one workgroup per CU) from about one and a half rounds of them over the 256
+  // CUs.  A tile 320 columns wide is taken where it needs no more tile area x rounds than a 256-wide one (hidden
+  // sizes that are multiples of 320 but not of 256, such as 1280).  The kernel addresses its operands in bytes, 32 bits.
   const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
-  if (big_tiles >= 512 && (a.n >= 2560 || a.k >= 2560 || big_tiles >= 1024)) {
-    // one workgroup per CU and 256 CUs: the launch takes ceil(tiles / 256) rounds of one tile
-    // time each.  A tile 320 columns wide is taken where it saves rounds' worth of tile area
-    // (hidden sizes that are multiples of 320 but not of 256, such as 1280).
+  if (big_tiles >= 400 && a.k >= 128 && a.m >= 256 && a.n >= 320 && a.epi != EPI_PARTIAL &&
+      (double)a.m * (double)a.lda < 2147483648.0 && (double)a.n * (double)a.k < 2147483648.0) {
     auto area = [&](int64_t bm, int64_t bn) {
       const int64_t t = ((a.m + bm - 1) / bm) * ((a.n + bn - 1) / bn);
       return ((t + 255) / 256) * bm * bn;
     };
-    if (area(256, 320) * 100 < area(256, 256) * 97) return launch_cfg<256, 320, 4, 2, 64, 2, 1>(a, s);
-    return launch_cfg<256, 256, 2, 4, 64, 2, 1>(a, s);
+    if (area(256, 320) <= area(256, 256)) return launch_persist<256, 320, 4, 2>(a, s);
+    return launch_persist<256, 256, 2, 4>(a, s);
   }
   // a single small request: fewer than 200 tiles of 128x128 leave most CUs idle; 64x64 tiles
   // (2 waves) quadruple the number of workgroups
   const int64_t mid_tiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);
-  if (mid_tiles < 200 && a.epi == EPI_RESID && a.partial && a.k >= 2048 && (a.k / 64) % 4 == 0 && a.n % 4 == 0) {
+  if (mid_tiles < 200 && a.epi == EPI_RESID && a.partial && a.k >= 2048 && (a.k / 64) % 4 == 0 && a.n % 8 == 0) {
     // a long contraction over few rows (fc2 of one small request): 64x64 tiles would each walk all of k and
     // re-read both operands from L2 twice as often; 128x128 tiles over a quarter of k each give as many
     // workgroups with a quarter of the iterations.  The slices are added to C in a fixed order afterwards.

@@ -23,17 +23,19 @@ import oracle  # noqa: E402
 import workloads  # noqa: E402
 
 
-def sample_rows(cu, n_rows_total, per_seg_div, n=24):
-    """First and last output row of the first, longest and last segments, plus seeded random rows."""
+def sample_rows(cu, n_rows_total, per_seg_div, n_random=64):
+    """First, middle and last output row of EVERY segment, plus seeded random rows.
+
+    (Files written before this rule hold 24 rows: first/last rows of the first, longest,
+    shortest and last segment plus random ones.  A file records the rows it holds, so the
+    test reads either kind.)"""
     rng = np.random.default_rng(12345)
     seg = [(int(a) // per_seg_div, int(b) // per_seg_div) for a, b in zip(cu[:-1], cu[1:]) if b > a]
-    lens = [b - a for a, b in seg]
-    pick = {seg[0][0], seg[0][1] - 1, seg[-1][0], seg[-1][1] - 1}
-    lo = seg[int(np.argmax(lens))]
-    pick |= {lo[0], lo[1] - 1, (lo[0] + lo[1]) // 2}
-    sh = seg[int(np.argmin(lens))]
-    pick |= {sh[0], sh[1] - 1}
-    while len(pick) < min(n, n_rows_total):
+    pick = set()
+    for a, b in seg:
+        pick |= {a, (a + b) // 2, b - 1}
+    want = min(len(pick) + n_random, n_rows_total)
+    while len(pick) < want:
         pick.add(int(rng.integers(0, n_rows_total)))
     return np.array(sorted(pick), np.int64)
 
