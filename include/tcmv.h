@@ -16,20 +16,20 @@
  * General rules
  *  - Every pointer whose name starts with d_ (and every pointer inside
  *    tcmv_weights and tcmv_item) is a DEVICE pointer owned by the caller; all
- *    other pointers are host pointers.  The library never frees caller memory.
- *  - The only device memory the library itself allocates is the per-plan index
- *    metadata (a few ints per token), on the first device call that uses a plan;
- *    tcmv_plan_destroy releases it.
- *  - Kernels are enqueued on the caller's hipStream_t (passed as void*, NULL =
- *    default stream); no call synchronises the stream, except the first use of a
- *    plan, which uploads its metadata with a blocking copy.
+ *    other pointers are host pointers.  The library never allocates or frees
+ *    device memory: frames, patch rows, activations, workspaces, weights and the
+ *    device copy of a plan's index metadata (a few ints per token, see
+ *    tcmv_plan_upload) all belong to the caller.
+ *  - Kernels and copies are enqueued on the caller's hipStream_t (passed as
+ *    void*, NULL = default stream); no call synchronises the stream or the device.
  *  - Every function returns TCMV_OK (0) or a negative TCMV_E_* code; the text of
  *    the last error of a context is available from tcmv_last_error.  No C++
  *    exception crosses this boundary.
  *  - Matrices are row-major and contiguous.  Linear weights are stored
  *    [out_features, in_features] (the contraction dimension is contiguous):
  *    y = x * W^T + b.
- *  - A context is not thread-safe; use one per thread.  Plans are immutable.
+ *  - A context is not thread-safe; use one per thread.  Plans are immutable and
+ *    may be used for any number of stage calls.
  *
  * Element types
  *  dtype TCMV_BF16: matrices (w_pe, w_qkv, w_o, w_1, w_2, w_m1, w_m2) are bf16;
@@ -37,8 +37,9 @@
  *    are bf16; the encoder output (d_hidden) is fp32; the projector output is bf16.
  *  dtype TCMV_F32: everything is fp32.
  *
- * Token order (Sec. 2.2: images become "a grid of patches with standardized
- * dimensions"): frames are grouped by `tpatch` (a still image is repeated),
+ * Token order (Sec. 2.2: an image is cut into a grid of patches of one fixed
+ * size, which is why its token count hardly varies): frames are grouped by
+ * `tpatch` (a still image is repeated),
  * giving a grid (gt, gh, gw) = (n_frames/tpatch or 1, dst_h/patch, dst_w/patch).
  * merge == 1: rows ordered (t, h, w).  merge == 2: rows ordered
  * (t, h/2, w/2, h%2, w%2) so every 2x2 merge group is four consecutive rows.
@@ -119,9 +120,10 @@ typedef struct {
   float attn_scale; /* 0: scores are scaled by 1/sqrt(head size); > 0: by this value */
 } tcmv_model_desc;
 
-/* One request.  Text requests carry no frames (n_frames == 0), produce no
- * tokens and launch nothing ("for text requests preprocessing and encoding is
- * negligible", Sec. 3.3).  An image is n_frames == 1; a video needs n_frames to
+/* One request (Sec. 4.1, Workloads: every request carries one text, one image
+ * or one video).  Text requests carry no frames (n_frames == 0), produce no
+ * tokens and launch nothing (Sec. 3.3: these two stages cost a text request
+ * next to nothing).  An image is n_frames == 1; a video needs n_frames to
  * be a multiple of tpatch.  d_frames: uint8 RGB interleaved
  * [n_frames, src_h, src_w, 3]; when (src_h, src_w) != (dst_h, dst_w) the frames
  * are resampled (integer bilinear, half-pixel centres, edge clamp, no
@@ -157,10 +159,13 @@ typedef struct {
   size_t encode_workspace_bytes; /* minimum workspace for tcmv_encode                 */
   size_t merge_workspace_bytes;  /* minimum workspace for tcmv_merge_project          */
   int n_items, n_segments;       /* n_segments: items with at least one token         */
+  size_t meta_bytes;             /* size of the plan's index metadata (tcmv_plan_upload); 0 for a plan without tokens */
 } tcmv_plan_info;
 
 /* major*100 + minor; 110 added the encoder-family fields at the end of tcmv_model_desc,
- * 120 head_dim and attn_scale behind them. */
+ * 120 head_dim and attn_scale behind them; 200: the caller owns the device copy of the plan
+ * metadata (tcmv_plan_upload, d_meta argument of the stage calls, meta_bytes) and the index
+ * data of tcmv_op_attention. */
 int tcmv_version(void);
 const char *tcmv_error_name(int code);
 
@@ -168,8 +173,10 @@ const char *tcmv_error_name(int code);
  * TCMV_BF16, to an even number for TCMV_F32.  Negative on an invalid description. */
 int64_t tcmv_k_pad(const tcmv_model_desc *desc);
 
-/* Validates the description (TCMV_E_INVALID_ARG / TCMV_E_UNSUPPORTED) and
- * creates a context.  Host only: works without a GPU. */
+/* One context per vision encoder (Table 1 of the paper lists the encoder families of
+ * its models; the description selects one).  Validates the description
+ * (TCMV_E_INVALID_ARG / TCMV_E_UNSUPPORTED) and creates a context.  Host only: works
+ * without a GPU. */
 int tcmv_create(const tcmv_model_desc *desc, tcmv_ctx **out);
 void tcmv_destroy(tcmv_ctx *ctx);
 /* Text of the last error of a context; with ctx == NULL, the reason of the last
@@ -180,18 +187,34 @@ const char *tcmv_last_error(const tcmv_ctx *ctx);
  * the context uses them).  Checks only for NULLs of required entries. */
 int tcmv_set_weights(tcmv_ctx *ctx, const tcmv_weights *w);
 
-/* Host only (no GPU needed; d_frames is not dereferenced).  Computes grids,
- * token order, cumulative segment lengths, per-row index maps and the attention
- * work list.  TCMV_E_BAD_SHAPE: dst not a positive multiple of patch*merge,
+/* One plan per batch of requests (Sec. 4.1, Workloads: one text, image or video per
+ * request; Sec. 2.2: an image becomes a grid of fixed-size patches, a video a
+ * sequence of sampled frames).  Host only (no GPU needed; d_frames is not
+ * dereferenced).  Computes grids, token order, cumulative segment lengths, per-row
+ * index maps and the attention work list.  TCMV_E_BAD_SHAPE: dst not a positive multiple of patch*merge,
  * video length not a multiple of tpatch, src size < 1 for an item with frames,
  * a segment longer than max_pos rows (LEARNED_1D) or a grid side above max_pos
  * (SEPARABLE_2D), a grid side above 255, or so many tokens that tokens x widest
- * activation row (max of 3d, mlp, merge^2 d, k_pad) reaches 2^32 (the kernels keep
+ * activation row (max of 3d, mlp, merge^2 d, k_pad) reaches 2^32, or the transposed
+ * values (heads x head size rows of padded token columns; with attention windows
+ * every window is padded to 64 columns) reach 2^32 elements (the kernels keep
  * element offsets in 32 bits; about 838 000 tokens at mlp = 5120).  Zero items,
- * or only text items, give a valid empty plan. */
+ * or only text items, give a valid empty plan.  Plans are immutable; the d_frames
+ * pointers are recorded in the plan's metadata. */
 int tcmv_plan_create(tcmv_ctx *ctx, const tcmv_item *items, int n_items, tcmv_plan **out);
 void tcmv_plan_destroy(tcmv_plan *plan);
 int tcmv_plan_query(const tcmv_plan *plan, tcmv_plan_info *info);
+/* The kernels read a plan's index metadata (row maps, work lists, the 3 x 256
+ * normalisation table, request descriptors) from a DEVICE buffer of meta_bytes bytes
+ * that the caller owns, 256-byte aligned, and hands to the stage calls as d_meta.
+ * tcmv_plan_meta returns the plan's host copy (lives as long as the plan) and its
+ * size, for callers that copy it themselves; tcmv_plan_upload enqueues the copy
+ * host -> d_meta on `stream` (hipMemcpyAsync from the plan's host copy: the plan must
+ * stay alive until the stream has passed the copy; TCMV_E_WORKSPACE_TOO_SMALL when
+ * meta_bytes is below tcmv_plan_info.meta_bytes).  One upload serves any number of
+ * stage calls. */
+const void *tcmv_plan_meta(const tcmv_plan *plan, size_t *bytes);
+int tcmv_plan_upload(const tcmv_plan *plan, void *d_meta, size_t meta_bytes, void *stream);
 /* cu_seqlens: host array of n_items+1 cumulative token counts (rows of the
  * encoder output per request; equal neighbours for text requests).  The pointer
  * lives as long as the plan. */
@@ -203,30 +226,36 @@ const int64_t *tcmv_plan_cu_seqlens(const tcmv_plan *plan);
  * Returns the number of entries, or a negative error. */
 int64_t tcmv_plan_row_map(const tcmv_plan *plan, int which, const int32_t **out);
 
-/* Stage 1 (Sec. 2.1 "preprocessed into intermediate representations"): resize
- * + normalise + patchify in one pass.  d_patches [n_patch_rows, k_pad], bf16 or
- * fp32 by dtype, 16-byte aligned; every element is written (padding columns
- * with zeros).
+/* Stage 1 (Sec. 2.1: visual inputs are first preprocessed into pixels or frames;
+ * Sec. 3.2 times this stage per request): resize + normalise + patchify in one
+ * pass.  d_meta: the device copy of the plan's metadata.  d_patches
+ * [n_patch_rows, k_pad], bf16 or fp32 by dtype, 16-byte aligned; every element is
+ * written (padding columns with zeros).
  * Integer / table arithmetic only: results are bit-exact by definition. */
-int tcmv_preprocess(tcmv_ctx *ctx, tcmv_plan *plan, void *d_patches, void *stream);
+int tcmv_preprocess(tcmv_ctx *ctx, const tcmv_plan *plan, const void *d_meta, void *d_patches, void *stream);
 
-/* Stage 2 (Sec. 2.1 "encoded into embeddings"): patch embedding (+CLS,
- * +position), `layers` pre-LN transformer blocks with bidirectional attention
- * restricted to each request's own tokens, optional final LayerNorm.
+/* Stage 2 (Sec. 2.1: the preprocessed input is then encoded into embeddings;
+ * Sec. 3.2 times this stage per request): patch embedding (+CLS, +position),
+ * `layers` pre-LN transformer blocks with bidirectional attention restricted to
+ * each request's own tokens, optional final LayerNorm.  d_meta as above.
  * d_hidden [n_tokens, d] fp32 receives the result.  d_workspace: scratch of at
  * least encode_workspace_bytes, 256-byte aligned, contents undefined after. */
-int tcmv_encode(tcmv_ctx *ctx, tcmv_plan *plan, const void *d_patches, void *d_hidden,
+int tcmv_encode(tcmv_ctx *ctx, const tcmv_plan *plan, const void *d_meta, const void *d_patches, void *d_hidden,
                 void *d_workspace, size_t workspace_bytes, void *stream);
 
-/* Stage 3: LayerNorm, concatenate each merge^2 consecutive rows, two-layer MLP
- * with GELU to out_dim.  d_out [n_out_tokens, out_dim] in the model dtype.
+/* Stage 3 (Sec. 2.1 and Fig. 1: the encoder's embeddings reach the LLM backend in
+ * one common format, next to the text embeddings, i.e. at the LLM's hidden size):
+ * LayerNorm, concatenate each merge^2 consecutive rows, two-layer MLP with GELU to
+ * out_dim.  d_out [n_out_tokens, out_dim] in the model dtype.
  * TCMV_E_UNSUPPORTED when out_dim == 0. */
-int tcmv_merge_project(tcmv_ctx *ctx, tcmv_plan *plan, const void *d_hidden, void *d_out,
+int tcmv_merge_project(tcmv_ctx *ctx, const tcmv_plan *plan, const void *d_hidden, void *d_out,
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /* ---- per-kernel timing ------------------------------------------------------
- * When enabled, the three stage calls bracket every kernel launch with a pair of
- * HIP events on the caller's stream (host-side objects, no device memory).
+ * tcmv_profile_enable(ctx, classes): classes is a bit mask over the kernel classes
+ * below (bit TCMV_K_x), a negative value selects all of them, 0 switches timing off.
+ * The three stage calls then bracket every launch of a selected class with a pair
+ * of HIP events on the caller's stream (host-side objects, no device memory).
  * tcmv_profile_read waits for the recorded events, adds the elapsed
  * milliseconds and launch counts per kernel class to ms[] / launches[] (arrays
  * of TCMV_K_COUNT entries, overwritten) and forgets the events. */
@@ -234,7 +263,7 @@ enum {
   TCMV_K_PREPROCESS = 0, TCMV_K_EMBED_GEMM, TCMV_K_LAYERNORM, TCMV_K_QKV_GEMM, TCMV_K_ATTENTION,
   TCMV_K_OUT_GEMM, TCMV_K_FC1_GEMM, TCMV_K_FC2_GEMM, TCMV_K_MERGE_GEMM, TCMV_K_OTHER, TCMV_K_COUNT
 };
-int tcmv_profile_enable(tcmv_ctx *ctx, int on);
+int tcmv_profile_enable(tcmv_ctx *ctx, int classes);
 int tcmv_profile_read(tcmv_ctx *ctx, double *ms, int64_t *launches);
 
 /* ---- single operators (the kernels the stages are built from), exposed so
@@ -249,8 +278,9 @@ int tcmv_op_layernorm(int dtype, const float *d_x, const float *d_gamma, const f
 
 /* C = epilogue(A * W^T + bias).  A [m, k], W [n, k], both bf16 (k % 64 == 0,
  * n % 8 == 0) or fp32.  epilogue: 0: store (bf16 / fp32 by dtype);
- * 1: GELU (erf form; the bf16 path evaluates it to within 3e-5 absolute) then
- * store; 2: d_c is fp32 [m, n] and is incremented
+ * 1: GELU (erf form; the bf16 path evaluates it to within 3.5e-5 absolute, and
+ * the bf16 result is within one unit in the last place of the rounded exact value
+ * or within 2^-22 of it) then store; 2: d_c is fp32 [m, n] and is incremented
  * (residual add); 5 (TCMV_BF16 only): gated product, output column j =
  * silu(column 2j) * column 2j+1, d_c is bf16 [m, n/2].  bias fp32 [n] or NULL. */
 int tcmv_op_gemm(int dtype, int epilogue, const void *d_a, const void *d_w, const float *d_bias,
@@ -259,10 +289,18 @@ int tcmv_op_gemm(int dtype, int epilogue, const void *d_a, const void *d_w, cons
 /* Block-diagonal bidirectional attention.  d_qkv [T, 3*d] (q | k | v thirds,
  * head j = columns [j*dh, (j+1)*dh) of each third), bf16 or fp32; cu_seqlens:
  * HOST array of n_seg+1 row offsets; d_out [T, d] same type as the input.
- * d_workspace / workspace_bytes: scratch, size from tcmv_op_attention_workspace. */
+ * The kernels read index data (row maps, work list) that depends on cu_seqlens only:
+ * tcmv_op_attention_index writes it into a HOST buffer of at least
+ * tcmv_op_attention_index_bytes bytes; the caller copies it to the device (d_index,
+ * 256-byte aligned) and may reuse it for any number of calls with the same shape.
+ * d_workspace / workspace_bytes: scratch, 256-byte aligned, size from
+ * tcmv_op_attention_workspace (0 from the size queries = invalid arguments). */
 size_t tcmv_op_attention_workspace(int dtype, const int64_t *cu_seqlens, int n_seg, int d, int heads);
-int tcmv_op_attention(int dtype, const void *d_qkv, const int64_t *cu_seqlens, int n_seg, int d,
-                      int heads, void *d_out, void *d_workspace, size_t workspace_bytes, void *stream);
+size_t tcmv_op_attention_index_bytes(int dtype, const int64_t *cu_seqlens, int n_seg, int d, int heads);
+int tcmv_op_attention_index(int dtype, const int64_t *cu_seqlens, int n_seg, int d, int heads, void *h_index,
+                            size_t index_bytes);
+int tcmv_op_attention(int dtype, const void *d_qkv, const int64_t *cu_seqlens, int n_seg, int d, int heads,
+                      const void *d_index, void *d_out, void *d_workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -47,7 +47,7 @@ class tcmv_plan_info(C.Structure):
                 ("k", C.c_int64), ("k_pad", C.c_int64),
                 ("patches_bytes", C.c_size_t), ("hidden_bytes", C.c_size_t), ("out_bytes", C.c_size_t),
                 ("encode_workspace_bytes", C.c_size_t), ("merge_workspace_bytes", C.c_size_t),
-                ("n_items", C.c_int), ("n_segments", C.c_int)]
+                ("n_items", C.c_int), ("n_segments", C.c_int), ("meta_bytes", C.c_size_t)]
 
 
 class TcmvError(RuntimeError):
@@ -70,8 +70,11 @@ SIGNATURES = {
     "tcmv_plan_query": (C.c_int, [C.c_void_p, C.POINTER(tcmv_plan_info)]),
     "tcmv_plan_cu_seqlens": (C.POINTER(C.c_int64), [C.c_void_p]),
     "tcmv_plan_row_map": (C.c_int64, [C.c_void_p, C.c_int, C.POINTER(C.POINTER(C.c_int32))]),
-    "tcmv_preprocess": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
-    "tcmv_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tcmv_plan_meta": (C.c_void_p, [C.c_void_p, C.POINTER(C.c_size_t)]),
+    "tcmv_plan_upload": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tcmv_preprocess": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tcmv_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                              C.c_void_p]),
     "tcmv_merge_project": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                      C.c_void_p]),
     "tcmv_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
@@ -81,8 +84,11 @@ SIGNATURES = {
     "tcmv_op_gemm": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                C.c_int, C.c_void_p]),
     "tcmv_op_attention_workspace": (C.c_size_t, [C.c_int, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int]),
+    "tcmv_op_attention_index_bytes": (C.c_size_t, [C.c_int, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int]),
+    "tcmv_op_attention_index": (C.c_int, [C.c_int, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                          C.c_size_t]),
     "tcmv_op_attention": (C.c_int, [C.c_int, C.c_void_p, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.c_void_p,
-                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
 
 _lib = None
@@ -210,13 +216,24 @@ def tcmv_plan_row_map(plan, which):
     return np.ctypeslib.as_array(p, shape=(n,)).copy()
 
 
-def tcmv_preprocess(ctx, plan, d_patches, stream=None):
-    _check(ctx, lib().tcmv_preprocess(ctx, plan, _ptr(d_patches), stream), "tcmv_preprocess")
+def tcmv_plan_meta(plan) -> bytes:
+    """Host copy of the plan's index metadata (what tcmv_plan_upload copies)."""
+    n = C.c_size_t()
+    p = lib().tcmv_plan_meta(plan, C.byref(n))
+    return C.string_at(p, n.value) if p and n.value else b""
 
 
-def tcmv_encode(ctx, plan, d_patches, d_hidden, d_workspace, workspace_bytes, stream=None):
-    _check(ctx, lib().tcmv_encode(ctx, plan, _ptr(d_patches), _ptr(d_hidden), _ptr(d_workspace), workspace_bytes,
-                                  stream), "tcmv_encode")
+def tcmv_plan_upload(ctx, plan, d_meta, meta_bytes, stream=None):
+    _check(ctx, lib().tcmv_plan_upload(plan, _ptr(d_meta), meta_bytes, stream), "tcmv_plan_upload")
+
+
+def tcmv_preprocess(ctx, plan, d_meta, d_patches, stream=None):
+    _check(ctx, lib().tcmv_preprocess(ctx, plan, _ptr(d_meta), _ptr(d_patches), stream), "tcmv_preprocess")
+
+
+def tcmv_encode(ctx, plan, d_meta, d_patches, d_hidden, d_workspace, workspace_bytes, stream=None):
+    _check(ctx, lib().tcmv_encode(ctx, plan, _ptr(d_meta), _ptr(d_patches), _ptr(d_hidden), _ptr(d_workspace),
+                                  workspace_bytes, stream), "tcmv_encode")
 
 
 def tcmv_merge_project(ctx, plan, d_hidden, d_out, d_workspace, workspace_bytes, stream=None):
@@ -228,8 +245,10 @@ KERNEL_CLASSES = ("preprocess", "embed_gemm", "layernorm", "qkv_gemm", "attentio
                   "fc2_gemm", "merge_gemm", "other")
 
 
-def tcmv_profile_enable(ctx, on):
-    _check(ctx, lib().tcmv_profile_enable(ctx, int(on)), "tcmv_profile_enable")
+def tcmv_profile_enable(ctx, classes):
+    """classes: bit mask over KERNEL_CLASSES (bit i = class i), -1 or True for all, 0 / False for off."""
+    classes = -1 if classes is True else int(classes)
+    _check(ctx, lib().tcmv_profile_enable(ctx, classes), "tcmv_profile_enable")
 
 
 def tcmv_profile_read(ctx):
@@ -259,10 +278,25 @@ def tcmv_op_attention_workspace(dtype, cu_seqlens, d, heads):
     return lib().tcmv_op_attention_workspace(dtype, arr, n, d, heads)
 
 
-def tcmv_op_attention(dtype, d_qkv, cu_seqlens, d, heads, d_out, d_workspace, workspace_bytes, stream=None):
+def tcmv_op_attention_index(dtype, cu_seqlens, d, heads) -> bytes:
+    """The index data of tcmv_op_attention for these segment lengths, as host bytes (the caller uploads them)."""
     n = len(cu_seqlens) - 1
     arr = (C.c_int64 * (n + 1))(*cu_seqlens)
-    rc = lib().tcmv_op_attention(dtype, _ptr(d_qkv), arr, n, d, heads, _ptr(d_out), _ptr(d_workspace),
+    nbytes = lib().tcmv_op_attention_index_bytes(dtype, arr, n, d, heads)
+    if nbytes == 0:
+        raise TcmvError(TCMV_E_INVALID_ARG, "tcmv_op_attention_index_bytes")
+    buf = C.create_string_buffer(nbytes)
+    rc = lib().tcmv_op_attention_index(dtype, arr, n, d, heads, buf, nbytes)
+    if rc != TCMV_OK:
+        raise TcmvError(rc, "tcmv_op_attention_index")
+    return buf.raw
+
+
+def tcmv_op_attention(dtype, d_qkv, cu_seqlens, d, heads, d_index, d_out, d_workspace, workspace_bytes, stream=None):
+    n = len(cu_seqlens) - 1
+    arr = (C.c_int64 * (n + 1))(*cu_seqlens)
+    rc = lib().tcmv_op_attention(dtype, _ptr(d_qkv), arr, n, d, heads, _ptr(d_index), _ptr(d_out), _ptr(d_workspace),
                                  workspace_bytes, stream)
     if rc != TCMV_OK:
         raise TcmvError(rc, "tcmv_op_attention")
+

@@ -23,7 +23,7 @@ struct tcmv_ctx {
   std::vector<const void*> layer;   // layers*12 device pointers (copied)
   std::string err;
   // per-kernel timing
-  bool profiling = false;
+  unsigned profile_mask = 0;         // bit c set: launches of kernel class c are bracketed with events
   struct Span { hipEvent_t a, b; int cat; };
   std::vector<Span> spans;          // recorded, not yet read
   std::vector<Span> free_spans;     // event pairs ready for reuse
@@ -52,8 +52,10 @@ struct tcmv_plan {
   int n_segments = 0;
   int bq = 0;                         // query rows per attention work item of the full-segment layers
   bool norm_bound = false, norm_bound_win = false;   // worth computing key norms (long segments / long windows)
-  // device copy (allocated on first device use)
-  uint8_t* d_meta = nullptr;
+  std::vector<int32_t> vt_pads;       // (first column, end column) of every padding run of the transposed-V buffer, both layouts
+  // index metadata as one blob (host copy owned by the plan; the caller keeps the device copy)
+  std::vector<uint8_t> blob;
+  size_t off_vt_pads = 0;
   size_t off_items = 0, off_prow_item = 0, off_prow_thw = 0, off_prow_dst = 0, off_prow_pos = 0, off_vcol = 0,
          off_cls = 0, off_work = 0, off_lut = 0, off_strips = 0, off_run_rows = 0, off_vcol_win = 0, off_work_win = 0,
          off_rope = 0, off_row_seg = 0, off_row_seg_win = 0, meta_bytes = 0;
@@ -164,9 +166,11 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   }
   w.h = off; off = align_up(off + T * d.mlp * e, 256);   // gated MLP: the product silu(gate)*up, also [T, mlp]
   // largest squared key norm per (segment or window, head)
-  // (+ one word behind the table: "some workgroup needs the reference-tracking kernel")
+  // (+ one word behind the table: "some workgroup needs the reference-tracking kernel").  Two such blocks: the
+  // layers that use the table alternate between them, and the attention kernel of one layer clears the block
+  // of the next.
   w.kmax_bytes = align_up(((size_t)std::max(p->n_segments, p->n_windows) * d.heads + 1) * 4, 256);
-  w.kmax = off; off += d.dtype == TCMV_BF16 ? w.kmax_bytes : 0;
+  w.kmax = off; off += d.dtype == TCMV_BF16 ? 2 * w.kmax_bytes : 0;
   // one small request: room for the four k-slices of the fc2 product (see GemmArgs::partial)
   const bool few_rows = d.dtype == TCMV_BF16 && ((T + 127) / 128) * (((size_t)d.d + 127) / 128) < 200;
   w.splitk_bytes = few_rows ? align_up(4 * T * (size_t)d.d * sizeof(float), 256) : 0;
@@ -194,39 +198,16 @@ size_t place(size_t& off, const std::vector<T>& v) {
   return at;
 }
 
-int ensure_uploaded(tcmv_ctx* ctx, tcmv_plan* p) {
-  if (p->d_meta || p->meta_bytes == 0) return TCMV_OK;
-  std::vector<uint8_t> blob(p->meta_bytes, 0);
-  auto put = [&](size_t off, const void* src, size_t n) { if (n) std::memcpy(blob.data() + off, src, n); };
-  put(p->off_items, p->items.data(), p->items.size() * sizeof(ItemDev));
-  put(p->off_prow_item, p->prow_item.data(), p->prow_item.size() * 4);
-  put(p->off_prow_thw, p->prow_thw.data(), p->prow_thw.size() * 4);
-  put(p->off_prow_dst, p->prow_dst.data(), p->prow_dst.size() * 4);
-  put(p->off_prow_pos, p->prow_pos.data(), p->prow_pos.size() * 4);
-  put(p->off_vcol, p->row_vcol.data(), p->row_vcol.size() * 4);
-  put(p->off_cls, p->cls_rows.data(), p->cls_rows.size() * 4);
-  put(p->off_work, p->work.data(), p->work.size() * sizeof(AttnWork));
-  put(p->off_lut, p->lut.data(), p->lut.size() * 4);
-  put(p->off_strips, p->strips.data(), p->strips.size() * sizeof(PreStrip));
-  put(p->off_run_rows, p->run_rows.data(), p->run_rows.size() * 4);
-  put(p->off_vcol_win, p->row_vcol_win.data(), p->row_vcol_win.size() * 4);
-  put(p->off_work_win, p->work_win.data(), p->work_win.size() * sizeof(AttnWork));
-  put(p->off_rope, p->rope.data(), p->rope.size() * 4);
-  put(p->off_row_seg, p->row_seg.data(), p->row_seg.size() * 4);
-  put(p->off_row_seg_win, p->row_seg_win.data(), p->row_seg_win.size() * 4);
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_meta), p->meta_bytes);
-  if (e != hipSuccess) { p->d_meta = nullptr; return fail_hip(ctx, e, "hipMalloc(plan metadata)"); }
-  e = hipMemcpy(p->d_meta, blob.data(), p->meta_bytes, hipMemcpyHostToDevice);
-  if (e != hipSuccess) {
-    (void)hipFree(p->d_meta);
-    p->d_meta = nullptr;
-    return fail_hip(ctx, e, "hipMemcpy(plan metadata)");
-  }
+template <class T>
+const T* dev(const void* d_meta, size_t off) { return reinterpret_cast<const T*>(reinterpret_cast<const uint8_t*>(d_meta) + off); }
+
+// checks the caller's device copy of the plan metadata
+int check_meta(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_meta) {
+  if (p->meta_bytes == 0) return TCMV_OK;
+  if (!d_meta) return fail(ctx, TCMV_E_INVALID_ARG, "null plan metadata buffer (see tcmv_plan_upload)");
+  if (reinterpret_cast<uintptr_t>(d_meta) % 256) return fail(ctx, TCMV_E_INVALID_ARG, "plan metadata buffer must be 256-byte aligned");
   return TCMV_OK;
 }
-
-template <class T>
-const T* dev(const tcmv_plan* p, size_t off) { return reinterpret_cast<const T*>(p->d_meta + off); }
 
 void build_work(std::vector<AttnWork>& work, const std::vector<int64_t>& seg_start, const std::vector<int64_t>& seg_len,
                 const std::vector<int64_t>& seg_v0, int bq) {
@@ -250,7 +231,7 @@ void build_work(std::vector<AttnWork>& work, const std::vector<int64_t>& seg_sta
 // Runs `launch` and, when timing is on, brackets it with an event pair.
 template <class F>
 hipError_t timed(tcmv_ctx* ctx, int cat, hipStream_t s, F&& launch) {
-  if (!ctx->profiling) return launch();
+  if (!((ctx->profile_mask >> cat) & 1u)) return launch();
   tcmv_ctx::Span sp{};
   if (!ctx->free_spans.empty()) {
     sp = ctx->free_spans.back();
@@ -278,7 +259,7 @@ hipError_t run_gemm(const tcmv_ctx* ctx, const GemmArgs& g, hipStream_t s) {
 
 extern "C" {
 
-int tcmv_version(void) { return 120; }   // 110: tcmv_model_desc gained the encoder-family switches; 120: head_dim, attn_scale
+int tcmv_version(void) { return 200; }   // see include/tcmv.h
 
 const char* tcmv_error_name(int code) {
   switch (code) {
@@ -323,9 +304,9 @@ void tcmv_destroy(tcmv_ctx* ctx) {
   delete ctx;
 }
 
-int tcmv_profile_enable(tcmv_ctx* ctx, int on) {
+int tcmv_profile_enable(tcmv_ctx* ctx, int classes) {
   if (!ctx) return TCMV_E_INVALID_ARG;
-  ctx->profiling = on != 0;
+  ctx->profile_mask = classes < 0 ? ~0u : (unsigned)classes;
   return TCMV_OK;
 }
 
@@ -461,6 +442,7 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
             win_start.push_back(row0 + local);
             win_len.push_back(n_win);
             win_v0.push_back(p->t_vpad_win);
+            if (n_win % kVtAlign) { p->vt_pads.push_back((int32_t)(p->t_vpad_win + (n_win & ~(int64_t)15))); p->vt_pads.push_back((int32_t)(p->t_vpad_win + (n_win + kVtAlign - 1) / kVtAlign * kVtAlign)); }
             for (int64_t r = 0; r < n_win; ++r) {
               p->row_vcol_win.push_back((int32_t)(p->t_vpad_win + vt_col_in_segment(r)));
               p->row_seg_win.push_back((int32_t)(win_start.size() - 1));
@@ -475,6 +457,9 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     seg_start.push_back(row0);
     seg_len.push_back(rows);
     seg_v0.push_back(p->t_vpad);
+    // columns that no key of the segment is written to: from the last (partly filled) group of 16 keys, whose
+    // quarters are interleaved, to the end of the 64-column padding
+    if (rows % kVtAlign) { p->vt_pads.push_back((int32_t)(p->t_vpad + (rows & ~(int64_t)15))); p->vt_pads.push_back((int32_t)(p->t_vpad + (rows + kVtAlign - 1) / kVtAlign * kVtAlign)); }
     for (int64_t r = 0; r < rows; ++r) {
       p->row_vcol.push_back((int32_t)(p->t_vpad + vt_col_in_segment(r)));
       p->row_seg.push_back((int32_t)(seg_start.size() - 1));
@@ -491,6 +476,9 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     const int64_t widest = std::max<int64_t>({3LL * d.d, 3LL * attn_width_of(d), (int64_t)d.mlp, m2 * d.d, k_pad_of(d)});
     if ((double)(p->t_vpad + kVtAlign) * (double)widest >= 4294967296.0)
       return bad("too many tokens in one plan: tokens x widest activation row (max of 3d, mlp, merge^2 d, k_pad) must stay below 2^32");
+    // the transposed values: heads x head size rows of ldvt() columns (every window padded to 64 columns)
+    if ((double)(p->ldvt() + kVtAlign) * (double)attn_width_of(d) >= 4294967296.0)
+      return bad("too many tokens in one plan: the transposed values (padded columns x attention width) must stay below 2^32 elements");
   }
   p->n_segments = (int)seg_start.size();
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), d.heads, seg_len) : kAttnBQ_f32;
@@ -532,15 +520,51 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->off_rope = place(off, p->rope);
   p->off_row_seg = place(off, p->row_seg);
   p->off_row_seg_win = place(off, p->row_seg_win);
-  p->meta_bytes = off;
+  p->off_vt_pads = place(off, p->vt_pads);
+  p->meta_bytes = p->n_patch_rows > 0 ? off : 0;
+  {
+    p->blob.assign(p->meta_bytes, 0);
+    auto put = [&](size_t at, const void* src, size_t n) { if (n && p->meta_bytes) std::memcpy(p->blob.data() + at, src, n); };
+    put(p->off_items, p->items.data(), p->items.size() * sizeof(ItemDev));
+    put(p->off_prow_item, p->prow_item.data(), p->prow_item.size() * 4);
+    put(p->off_prow_thw, p->prow_thw.data(), p->prow_thw.size() * 4);
+    put(p->off_prow_dst, p->prow_dst.data(), p->prow_dst.size() * 4);
+    put(p->off_prow_pos, p->prow_pos.data(), p->prow_pos.size() * 4);
+    put(p->off_vcol, p->row_vcol.data(), p->row_vcol.size() * 4);
+    put(p->off_cls, p->cls_rows.data(), p->cls_rows.size() * 4);
+    put(p->off_work, p->work.data(), p->work.size() * sizeof(AttnWork));
+    put(p->off_lut, p->lut.data(), p->lut.size() * 4);
+    put(p->off_strips, p->strips.data(), p->strips.size() * sizeof(PreStrip));
+    put(p->off_run_rows, p->run_rows.data(), p->run_rows.size() * 4);
+    put(p->off_vcol_win, p->row_vcol_win.data(), p->row_vcol_win.size() * 4);
+    put(p->off_work_win, p->work_win.data(), p->work_win.size() * sizeof(AttnWork));
+    put(p->off_rope, p->rope.data(), p->rope.size() * 4);
+    put(p->off_row_seg, p->row_seg.data(), p->row_seg.size() * 4);
+    put(p->off_row_seg_win, p->row_seg_win.data(), p->row_seg_win.size() * 4);
+    put(p->off_vt_pads, p->vt_pads.data(), p->vt_pads.size() * 4);
+  }
   *out = p;
   return TCMV_OK;
 }
 
-void tcmv_plan_destroy(tcmv_plan* plan) {
-  if (!plan) return;
-  if (plan->d_meta) (void)hipFree(plan->d_meta);
-  delete plan;
+void tcmv_plan_destroy(tcmv_plan* plan) { delete plan; }
+
+const void* tcmv_plan_meta(const tcmv_plan* p, size_t* bytes) {
+  if (!p) return nullptr;
+  if (bytes) *bytes = p->meta_bytes;
+  return p->meta_bytes ? p->blob.data() : nullptr;
+}
+
+int tcmv_plan_upload(const tcmv_plan* p, void* d_meta, size_t meta_bytes, void* stream) {
+  if (!p) return TCMV_E_INVALID_ARG;
+  tcmv_ctx* ctx = p->ctx;
+  if (p->meta_bytes == 0) return TCMV_OK;
+  if (!d_meta) return fail(ctx, TCMV_E_INVALID_ARG, "null plan metadata buffer");
+  if (reinterpret_cast<uintptr_t>(d_meta) % 256) return fail(ctx, TCMV_E_INVALID_ARG, "plan metadata buffer must be 256-byte aligned");
+  if (meta_bytes < p->meta_bytes) return fail(ctx, TCMV_E_WORKSPACE_TOO_SMALL, "plan metadata buffer too small");
+  const hipError_t e = hipMemcpyAsync(d_meta, p->blob.data(), p->meta_bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync(plan metadata)");
+  return TCMV_OK;
 }
 
 int tcmv_plan_query(const tcmv_plan* p, tcmv_plan_info* info) {
@@ -560,6 +584,7 @@ int tcmv_plan_query(const tcmv_plan* p, tcmv_plan_info* info) {
   info->merge_workspace_bytes = d.out_dim ? merge_ws(p).total : 0;
   info->n_items = (int)p->items.size();
   info->n_segments = p->n_segments;
+  info->meta_bytes = p->meta_bytes;
   return TCMV_OK;
 }
 
@@ -578,7 +603,7 @@ int64_t tcmv_plan_row_map(const tcmv_plan* p, int which, const int32_t** out) {
   return (int64_t)v->size();
 }
 
-int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) {
+int tcmv_preprocess(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_meta, void* d_patches, void* stream) {
   if (!ctx) return TCMV_E_INVALID_ARG;
   if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
   if (p->n_patch_rows == 0) return TCMV_OK;
@@ -586,28 +611,28 @@ int tcmv_preprocess(tcmv_ctx* ctx, tcmv_plan* p, void* d_patches, void* stream) 
   if (reinterpret_cast<uintptr_t>(d_patches) % 16) return fail(ctx, TCMV_E_INVALID_ARG, "patch buffer must be 16-byte aligned");
   for (const ItemDev& it : p->items)
     if (it.n_frames > 0 && !it.frames) return fail(ctx, TCMV_E_INVALID_ARG, "an item with frames has a null frame pointer");
-  int rc = ensure_uploaded(ctx, p);
+  const int rc = check_meta(ctx, p, d_meta);
   if (rc != TCMV_OK) return rc;
   PreprocArgs a{};
-  a.items = dev<ItemDev>(p, p->off_items);
-  a.prow_item = dev<int32_t>(p, p->off_prow_item);
-  a.prow_thw = dev<int32_t>(p, p->off_prow_thw);
-  a.lut = dev<float>(p, p->off_lut);
+  a.items = dev<ItemDev>(d_meta, p->off_items);
+  a.prow_item = dev<int32_t>(d_meta, p->off_prow_item);
+  a.prow_thw = dev<int32_t>(d_meta, p->off_prow_thw);
+  a.lut = dev<float>(d_meta, p->off_lut);
   a.patches = d_patches;
   a.rows = p->n_patch_rows;
   a.patch = ctx->desc.patch; a.tpatch = ctx->desc.tpatch;
   a.k = (int)ctx->k; a.k_pad = (int)ctx->k_pad;
   a.out_bf16 = ctx->desc.dtype == TCMV_BF16;
   a.merge = ctx->desc.merge;
-  a.strips = dev<PreStrip>(p, p->off_strips); a.n_strips = (int)p->strips.size();
-  a.run_rows = dev<int32_t>(p, p->off_run_rows); a.n_run_rows = (int64_t)p->run_rows.size();
+  a.strips = dev<PreStrip>(d_meta, p->off_strips); a.n_strips = (int)p->strips.size();
+  a.run_rows = dev<int32_t>(d_meta, p->off_run_rows); a.n_run_rows = (int64_t)p->run_rows.size();
   hipError_t e = timed(ctx, TCMV_K_PREPROCESS, (hipStream_t)stream, [&] { return launch_preprocess(a, (hipStream_t)stream); });
   if (e != hipSuccess) return fail_hip(ctx, e, "preprocess launch");
   return TCMV_OK;
 }
 
-int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidden, void* d_workspace,
-                size_t workspace_bytes, void* stream) {
+int tcmv_encode(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_meta, const void* d_patches, void* d_hidden,
+                void* d_workspace, size_t workspace_bytes, void* stream) {
   if (!ctx) return TCMV_E_INVALID_ARG;
   if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
   if (!ctx->has_weights) return fail(ctx, TCMV_E_NO_WEIGHTS, "tcmv_set_weights has not been called");
@@ -616,7 +641,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return fail(ctx, TCMV_E_INVALID_ARG, "workspace not 256-byte aligned");
   const EncodeWs ws = encode_ws(p);
   if (workspace_bytes < ws.total) return fail(ctx, TCMV_E_WORKSPACE_TOO_SMALL, "encode workspace too small");
-  int rc = ensure_uploaded(ctx, p);
+  const int rc = check_meta(ctx, p, d_meta);
   if (rc != TCMV_OK) return rc;
 
   const tcmv_model_desc& d = ctx->desc;
@@ -634,21 +659,27 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   hipError_t e;
 #define TCMV_CHECK(call, what) do { e = (call); if (e != hipSuccess) return fail_hip(ctx, e, what); } while (0)
 
-  // the padding columns of the transposed-V buffer must read as zeros in every layer
+  // The padding columns of the transposed-V buffer must never hold NaN or infinity bit patterns (their
+  // probabilities are zero, and 0 * NaN is NaN): they are cleared once, for both column layouts.  Both key-norm
+  // blocks start at zero.
   if (bf)
-    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(vt, (size_t)da * p->ldvt() * 2, s); }), "V^T clear");
+    TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
+                 return launch_attn_prepare(vt, p->ldvt(), da, dev<int32_t>(d_meta, p->off_vt_pads), (int)(p->vt_pads.size() / 2),
+                                            reinterpret_cast<uint32_t*>(wsb + ws.kmax), (int)(2 * ws.kmax_bytes / 4), s); }),
+               "attention set-up");
+  int kblock = 0;                                  // key-norm block of the next layer that uses one
   // patch embedding (+ position), CLS rows
   {
     GemmArgs g{};
     g.a = d_patches; g.lda = ctx->k_pad; g.w = ctx->w.w_pe; g.bias = reinterpret_cast<const float*>(ctx->w.b_pe);
     g.c = x; g.ldc = d.d; g.m = p->n_patch_rows; g.n = d.d; g.k = (int)ctx->k_pad; g.epi = EPI_EMBED;
-    g.dst_row = dev<int32_t>(p, p->off_prow_dst); g.pos_idx = dev<int32_t>(p, p->off_prow_pos);
+    g.dst_row = dev<int32_t>(d_meta, p->off_prow_dst); g.pos_idx = dev<int32_t>(d_meta, p->off_prow_pos);
     g.pos0 = reinterpret_cast<const float*>(ctx->w.pos0); g.pos1 = reinterpret_cast<const float*>(ctx->w.pos1);
     g.pos_kind = d.pos;
     TCMV_CHECK(timed(ctx, TCMV_K_EMBED_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "patch-embed GEMM");
     if (d.use_cls)
       TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
-                   return launch_cls_rows(x, dev<int32_t>(p, p->off_cls), (int)p->cls_rows.size(),
+                   return launch_cls_rows(x, dev<int32_t>(d_meta, p->off_cls), (int)p->cls_rows.size(),
                                           reinterpret_cast<const float*>(ctx->w.cls),
                                           d.pos == TCMV_POS_LEARNED_1D ? reinterpret_cast<const float*>(ctx->w.pos0) : nullptr,
                                           d.d, s); }), "CLS rows");
@@ -658,24 +689,41 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
     auto f = [&](int j) { return reinterpret_cast<const float*>(L[j]); };
     const bool windowed = d.window && !(d.full_every && (l + 1) % d.full_every == 0);
     TCMV_CHECK(timed(ctx, TCMV_K_LAYERNORM, s, [&] { return launch_layernorm(x, f(0), f(1), xn, T, d.d, d.ln_eps, bf, s, d.norm); }), "LN1");
+    bool use_kmax = false, kmax_fused = false;
+    uint32_t *kmax = nullptr, *kmax_other = nullptr;
+    const int32_t* row_seg = nullptr;
     {
       GemmArgs g{};
       g.a = xn; g.lda = d.d; g.w = L[2]; g.bias = f(3); g.m = T; g.n = 3 * da; g.k = d.d;
       g.c = qkv; g.epi = EPI_QKV;
       if (bf) {
         g.ldc = 2 * da; g.split = 2 * da; g.vt = vt; g.ldvt = p->ldvt();
-        g.vcol = dev<int32_t>(p, windowed ? p->off_vcol_win : p->off_vcol);
-        if (d.pos == TCMV_POS_ROTARY_2D) { g.rope = dev<float>(p, p->off_rope); g.rope_dh = dh; }
+        g.vcol = dev<int32_t>(d_meta, windowed ? p->off_vcol_win : p->off_vcol);
+        if (d.pos == TCMV_POS_ROTARY_2D) { g.rope = dev<float>(d_meta, p->off_rope); g.rope_dh = dh; }
         // the queries leave the projection already multiplied by softmax scale * log2(e)
         g.qcols = da; g.qscale = (float)(1.4426950408889634 * attn_scale_of(d));
+        // largest key norm per (segment, head): lets the attention kernel drop the running maximum where the
+        // scores are provably small.  The projection's epilogue computes it where its tiles line up with the heads.
+        const bool short_windows = windowed && p->max_win_len <= 64;
+        use_kmax = !short_windows && (windowed ? p->norm_bound_win : p->norm_bound);
+        if (use_kmax) {
+          kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax + (size_t)kblock * ws.kmax_bytes);
+          kmax_other = reinterpret_cast<uint32_t*>(wsb + ws.kmax + (size_t)(kblock ^ 1) * ws.kmax_bytes);
+          kblock ^= 1;
+          row_seg = dev<int32_t>(d_meta, windowed ? p->off_row_seg_win : p->off_row_seg);
+          if (gemm_bf16_can_fuse_key_norms(T, 3 * da, d.d, da, dh)) {
+            g.kmax2 = kmax; g.row_seg = row_seg; g.kn_dh = dh; g.kn_heads = d.heads;
+            kmax_fused = true;
+          }
+        }
       }
       else { g.ldc = 3 * d.d; }
       TCMV_CHECK(timed(ctx, TCMV_K_QKV_GEMM, s, [&] { return run_gemm(ctx, g, s); }), "QKV GEMM");
     }
     {
       AttnArgs a{};
-      if (windowed) { a.work = dev<AttnWork>(p, p->off_work_win); a.n_work = (int)p->work_win.size(); }
-      else { a.work = dev<AttnWork>(p, p->off_work); a.n_work = (int)p->work.size(); }
+      if (windowed) { a.work = dev<AttnWork>(d_meta, p->off_work_win); a.n_work = (int)p->work_win.size(); }
+      else { a.work = dev<AttnWork>(d_meta, p->off_work); a.n_work = (int)p->work.size(); }
       a.heads = d.heads; a.dh = dh; a.t_total = T; a.out = xn; a.ldo = da;
       a.bq = windowed ? kAttnBQ_window : p->bq;
       if (bf) {
@@ -684,17 +732,13 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
         a.scale = 1.0f; a.prescaled = 1;
         // windows of at most 64 tokens (8 x 8 patches): one small workgroup per window and head
         const bool short_windows = windowed && p->max_win_len <= 64;
-        // largest key norm per (segment, head): lets the attention kernel drop the running maximum where
-        // the scores are provably small
-        if (!short_windows && (windowed ? p->norm_bound_win : p->norm_bound)) {
-          uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + ws.kmax);
-          TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] { return launch_fill_zero(kmax, ws.kmax_bytes, s); }), "key-norm clear");
-          TCMV_CHECK(timed(ctx, TCMV_K_OTHER, s, [&] {
-                       return launch_knorm(qk + da, 2 * da, T, d.heads, dh,
-                                           dev<int32_t>(p, windowed ? p->off_row_seg_win : p->off_row_seg), kmax, s); }),
-                     "key norms");
+        if (use_kmax) {
+          if (!kmax_fused)
+            TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_knorm(qk + da, 2 * da, T, d.heads, dh, row_seg, kmax, s); }),
+                       "key norms");
           a.kmax2 = kmax;
           a.any_left = kmax + (size_t)std::max(p->n_segments, p->n_windows) * d.heads;
+          a.kmax_clear = kmax_other; a.n_clear = (int)(ws.kmax_bytes / 4);
         }
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return short_windows ? launch_attn_window_bf16(a, s) : launch_attn_bf16(a, s); }),
                    "attention");
@@ -735,7 +779,7 @@ int tcmv_encode(tcmv_ctx* ctx, tcmv_plan* p, const void* d_patches, void* d_hidd
   return TCMV_OK;
 }
 
-int tcmv_merge_project(tcmv_ctx* ctx, tcmv_plan* p, const void* d_hidden, void* d_out, void* d_workspace,
+int tcmv_merge_project(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_hidden, void* d_out, void* d_workspace,
                        size_t workspace_bytes, void* stream) {
   if (!ctx) return TCMV_E_INVALID_ARG;
   if (!p || p->ctx != ctx) return fail(ctx, TCMV_E_INVALID_ARG, "plan does not belong to this context");
@@ -805,7 +849,9 @@ int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, cons
 }
 
 namespace {
-struct OpAttnLayout { size_t vcol, work, vt, rseg, kmax, kmax_bytes, total; int64_t t_vpad; int64_t T; int bq; size_t n_seg; };
+// Index data (built on the host, uploaded by the caller): [row -> transposed-V column][work list][row -> segment].
+// Scratch: [transposed V][key-norm table + flag].
+struct OpAttnLayout { size_t vcol, work, rseg, index_total; size_t vt, kmax, kmax_bytes, ws_total; int64_t t_vpad; int64_t T; int bq; size_t n_seg; size_t n_work; };
 OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int heads, std::vector<int32_t>* vcol,
                             std::vector<AttnWork>* work, std::vector<int32_t>* rseg = nullptr) {
   OpAttnLayout L{};
@@ -835,13 +881,16 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   size_t off = 0;
   L.vcol = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
   L.work = off; off = align_up(off + std::max<size_t>(wtmp.size() * sizeof(AttnWork), 16), 256);
+  L.rseg = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
+  L.index_total = off;
+  off = 0;
   L.vt = off;
   if (dtype == TCMV_BF16) off = align_up(off + (size_t)d * vp * 2, 256);
-  L.rseg = off; off = align_up(off + std::max<size_t>((size_t)L.T * 4, 16), 256);
   L.kmax_bytes = align_up((ss.size() * (size_t)heads + 1) * 4, 256);
   L.kmax = off; off += L.kmax_bytes;
+  L.ws_total = off;
   L.n_seg = ss.size();
-  L.total = off;
+  L.n_work = wtmp.size();
   if (work) work->swap(wtmp);
   return L;
 }
@@ -852,52 +901,33 @@ bool cu_ok(const int64_t* cu, int n_seg) {
     if (cu[s + 1] < cu[s]) return false;
   return cu[n_seg] < (1LL << 30);
 }
-}  // namespace
-
-size_t tcmv_op_attention_workspace(int dtype, const int64_t* cu_seqlens, int n_seg, int d, int heads) {
-  if (!cu_ok(cu_seqlens, n_seg) || d <= 0 || heads <= 0) return 0;
-  return op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr).total;
+bool op_attn_args_ok(int dtype, const int64_t* cu, int n_seg, int d, int heads) {
+  return (dtype == TCMV_F32 || dtype == TCMV_BF16) && cu_ok(cu, n_seg) && d > 0 && heads > 0 && d % heads == 0;
 }
 
-int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads,
-                      void* d_out, void* d_workspace, size_t workspace_bytes, void* stream) {
-  if ((dtype != TCMV_F32 && dtype != TCMV_BF16) || !cu_ok(cu_seqlens, n_seg) || d <= 0 || heads <= 0 || d % heads)
-    return TCMV_E_INVALID_ARG;
+// the launches of tcmv_op_attention; `scratch` holds L.ws_total bytes
+int op_attention_run(int dtype, const void* d_qkv, int d, int heads, const OpAttnLayout& L, const void* d_index, void* d_out,
+                     uint8_t* scratch, hipStream_t s) {
   const int dh = d / heads;
-  if (dtype == TCMV_BF16 ? !(dh == 32 || dh == 64 || dh == 80 || dh == 96) : (dh % 16 || dh > 128)) return TCMV_E_UNSUPPORTED;
-  std::vector<int32_t> vcol, rseg;
-  std::vector<AttnWork> work;
-  const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work, &rseg);
-  if (L.T == 0) return TCMV_OK;
-  // the kernels keep element offsets into qkv and into the transposed values in 32 bits
-  if ((double)(L.t_vpad + kVtAlign) * 3.0 * (double)d >= 4294967296.0) return TCMV_E_UNSUPPORTED;
-  if (!d_qkv || !d_out || !d_workspace) return TCMV_E_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(d_workspace) % 256) return TCMV_E_INVALID_ARG;
-  if (workspace_bytes < L.total) return TCMV_E_WORKSPACE_TOO_SMALL;
-  hipStream_t s = (hipStream_t)stream;
-  uint8_t* wsb = reinterpret_cast<uint8_t*>(d_workspace);
-  // index data: blocking copies (this entry point is for checking and timing one kernel)
-  if (hipMemcpy(wsb + L.vcol, vcol.data(), vcol.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
-  if (hipMemcpy(wsb + L.work, work.data(), work.size() * sizeof(AttnWork), hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
-  if (hipMemcpy(wsb + L.rseg, rseg.data(), rseg.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return TCMV_E_HIP;
+  const uint8_t* idx = reinterpret_cast<const uint8_t*>(d_index);
   AttnArgs a{};
-  a.work = reinterpret_cast<const AttnWork*>(wsb + L.work); a.n_work = (int)work.size();
+  a.work = reinterpret_cast<const AttnWork*>(idx + L.work); a.n_work = (int)L.n_work;
   a.heads = heads; a.dh = dh; a.t_total = L.T; a.out = d_out; a.ldo = d;
   a.bq = L.bq;
   hipError_t e;
   if (dtype == TCMV_BF16) {
     const uint16_t* q = reinterpret_cast<const uint16_t*>(d_qkv);
-    e = launch_fill_zero(wsb + L.vt, (size_t)d * L.t_vpad * 2, s);
+    e = launch_fill_zero(scratch + L.vt, (size_t)d * L.t_vpad * 2, s);
     if (e != hipSuccess) return TCMV_E_HIP;
-    e = launch_transpose_v(q + 2 * d, 3 * d, reinterpret_cast<const int32_t*>(wsb + L.vcol), wsb + L.vt, L.t_vpad, L.T, d, s);
+    e = launch_transpose_v(q + 2 * d, 3 * d, reinterpret_cast<const int32_t*>(idx + L.vcol), scratch + L.vt, L.t_vpad, L.T, d, s);
     if (e != hipSuccess) return TCMV_E_HIP;
-    a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = wsb + L.vt; a.ldv = L.t_vpad;
+    a.q = q; a.k = q + d; a.ldqk = 3 * d; a.v = scratch + L.vt; a.ldv = L.t_vpad;
     a.scale = (float)(1.4426950408889634 / std::sqrt((double)dh));
     a.prescaled = 0;                               // the caller's queries are unscaled
-    uint32_t* kmax = reinterpret_cast<uint32_t*>(wsb + L.kmax);
+    uint32_t* kmax = reinterpret_cast<uint32_t*>(scratch + L.kmax);
     e = launch_fill_zero(kmax, L.kmax_bytes, s);
     if (e != hipSuccess) return TCMV_E_HIP;
-    e = launch_knorm(q + d, 3 * d, L.T, heads, dh, reinterpret_cast<const int32_t*>(wsb + L.rseg), kmax, s);
+    e = launch_knorm(q + d, 3 * d, L.T, heads, dh, reinterpret_cast<const int32_t*>(idx + L.rseg), kmax, s);
     if (e != hipSuccess) return TCMV_E_HIP;
     a.kmax2 = kmax;
     a.any_left = kmax + L.n_seg * (size_t)heads;
@@ -909,6 +939,56 @@ int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, i
     e = launch_attn_f32(a, s);
   }
   return e == hipSuccess ? TCMV_OK : TCMV_E_HIP;
+}
+
+// shape checks shared by the two attention entry points; fills L
+int op_attention_check(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads, const void* d_index,
+                       const void* d_out, OpAttnLayout* L) {
+  if (!op_attn_args_ok(dtype, cu_seqlens, n_seg, d, heads)) return TCMV_E_INVALID_ARG;
+  const int dh = d / heads;
+  if (dtype == TCMV_BF16 ? !(dh == 32 || dh == 64 || dh == 80 || dh == 96) : (dh % 16 || dh > 128)) return TCMV_E_UNSUPPORTED;
+  *L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr);
+  if (L->T == 0) return TCMV_OK;
+  // the kernels keep element offsets into qkv and into the transposed values in 32 bits
+  if ((double)(L->t_vpad + kVtAlign) * 3.0 * (double)d >= 4294967296.0) return TCMV_E_UNSUPPORTED;
+  if (!d_qkv || !d_out || !d_index) return TCMV_E_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(d_index) % 256) return TCMV_E_INVALID_ARG;
+  return TCMV_OK;
+}
+}  // namespace
+
+size_t tcmv_op_attention_workspace(int dtype, const int64_t* cu_seqlens, int n_seg, int d, int heads) {
+  if (!op_attn_args_ok(dtype, cu_seqlens, n_seg, d, heads)) return 0;
+  return op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr).ws_total;
+}
+
+size_t tcmv_op_attention_index_bytes(int dtype, const int64_t* cu_seqlens, int n_seg, int d, int heads) {
+  if (!op_attn_args_ok(dtype, cu_seqlens, n_seg, d, heads)) return 0;
+  return op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr).index_total;
+}
+
+int tcmv_op_attention_index(int dtype, const int64_t* cu_seqlens, int n_seg, int d, int heads, void* h_index, size_t index_bytes) {
+  if (!op_attn_args_ok(dtype, cu_seqlens, n_seg, d, heads) || !h_index) return TCMV_E_INVALID_ARG;
+  std::vector<int32_t> vcol, rseg;
+  std::vector<AttnWork> work;
+  const OpAttnLayout L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, &vcol, &work, &rseg);
+  if (index_bytes < L.index_total) return TCMV_E_WORKSPACE_TOO_SMALL;
+  uint8_t* h = reinterpret_cast<uint8_t*>(h_index);
+  std::memset(h, 0, L.index_total);
+  if (!vcol.empty()) std::memcpy(h + L.vcol, vcol.data(), vcol.size() * 4);
+  if (!work.empty()) std::memcpy(h + L.work, work.data(), work.size() * sizeof(AttnWork));
+  if (!rseg.empty()) std::memcpy(h + L.rseg, rseg.data(), rseg.size() * 4);
+  return TCMV_OK;
+}
+
+int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads,
+                      const void* d_index, void* d_out, void* d_workspace, size_t workspace_bytes, void* stream) {
+  OpAttnLayout L{};
+  const int rc = op_attention_check(dtype, d_qkv, cu_seqlens, n_seg, d, heads, d_index, d_out, &L);
+  if (rc != TCMV_OK || L.T == 0) return rc;
+  if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256) return TCMV_E_INVALID_ARG;
+  if (workspace_bytes < L.ws_total) return TCMV_E_WORKSPACE_TOO_SMALL;
+  return op_attention_run(dtype, d_qkv, d, heads, L, d_index, d_out, reinterpret_cast<uint8_t*>(d_workspace), (hipStream_t)stream);
 }
 
 }  // extern "C"

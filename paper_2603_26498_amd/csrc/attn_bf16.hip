@@ -87,6 +87,9 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   constexpr int WQ = 32 * NT;             // query rows per wave
   __shared__ __attribute__((aligned(16))) uint8_t smem[kStages * C::STAGE];
 
+  // the key-norm block of the next layer is cleared by the first workgroup of the first kernel of this launch
+  if (FAST && blockIdx.x == 0 && a.kmax_clear)
+    for (int i = threadIdx.x; i < a.n_clear; i += NTHREADS) a.kmax_clear[i] = 0u;
   const int total = a.n_work * a.heads;
   const int chunk = (total + 7) >> 3;
   const int p = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
@@ -590,6 +593,31 @@ hipError_t launch_knorm(const void* k, int64_t ldk, int64_t rows, int heads, int
   if (lds > 64 * 1024) return hipErrorInvalidValue;
   hipLaunchKernelGGL(knorm_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), lds, s,
                      reinterpret_cast<const uint16_t*>(k), ldk, rows, heads, cph, row_seg, kmax2);
+  return hipGetLastError();
+}
+
+// Start of an encode: zero the padding columns of the transposed-V buffer (block x = padding run, block y walks the
+// rows) and a block of 32-bit words (the key-norm tables).
+__global__ __launch_bounds__(256) void attn_prepare_kernel(uint16_t* vt, int64_t ldvt, int rows, const int32_t* pads, int n_pads,
+                                                           uint32_t* words, int n_words) {
+  if (blockIdx.x == 0 && blockIdx.y == 0)
+    for (int i = threadIdx.x; i < n_words; i += 256) words[i] = 0u;
+  if ((int)blockIdx.x >= n_pads) return;
+  const int c0 = pads[2 * blockIdx.x], c1 = pads[2 * blockIdx.x + 1];
+  const int w = c1 - c0;                             // at most 63 columns
+  for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < (int64_t)rows * w; i += (int64_t)gridDim.y * 256) {
+    const int64_t r = i / w;
+    vt[r * ldvt + c0 + (int)(i - r * w)] = 0;
+  }
+}
+
+hipError_t launch_attn_prepare(void* vt, int64_t ldvt, int rows, const int32_t* pads, int n_pads, uint32_t* words,
+                               int n_words, hipStream_t s) {
+  if (n_pads < 0 || n_words < 0 || n_pads > 65535 * 256) return hipErrorInvalidValue;
+  if (n_pads == 0 && n_words == 0) return hipSuccess;
+  const dim3 grid((unsigned)std::max(n_pads, 1), n_pads ? 8 : 1);
+  hipLaunchKernelGGL(attn_prepare_kernel, grid, dim3(256), 0, s, reinterpret_cast<uint16_t*>(vt), ldvt, rows, pads, n_pads,
+                     words, n_words);
   return hipGetLastError();
 }
 

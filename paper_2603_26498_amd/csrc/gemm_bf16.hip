@@ -53,6 +53,24 @@ constexpr int kEpStride = 68;                      // floats per row of a wave's
 constexpr int kEpWaveBytes = 32 * kEpStride * 4;   // staging bytes per wave
 }  // namespace
 
+// Lane exchanges inside a row of 16 lanes through the data-parallel path of the vector ALU (no LDS round trip):
+// value of lane (l ^ 1), lane (l ^ 2), lane (l + 4), lane (l + 8); lanes that would read past the row get 0.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float lane_xor1(float v) { return dpp_move<0xB1>(v); }   // quad_perm [1,0,3,2]
+__device__ __forceinline__ float lane_xor2(float v) { return dpp_move<0x4E>(v); }   // quad_perm [2,3,0,1]
+__device__ __forceinline__ float lane_up4(float v) { return dpp_move<0x104>(v); }   // row_shl:4
+__device__ __forceinline__ float lane_up8(float v) { return dpp_move<0x108>(v); }   // row_shl:8
+
+// *p = max(*p, v).  Thousands of waves update the few words of one table: the atomic is only issued when the word, as
+// this wave sees it, is smaller (a stale view only costs an atomic that changes nothing), which leaves a handful of
+// atomics per word instead of one per wave queued behind each other.
+__device__ __forceinline__ void table_max(uint32_t* p, uint32_t v) {
+  if (__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < v) atomicMax(p, v);   // the load bypasses the CU's own cache
+}
+
 // Rows and columns of the output that a workgroup may write: [row_lo, row_hi) x [col_lo, col_hi).
 struct TileBounds { int64_t row_lo, row_hi; int col_lo, col_hi; int slice; };
 
@@ -60,12 +78,21 @@ struct TileBounds { int64_t row_lo, row_hi; int col_lo, col_hi; int slice; };
 // accumulator a lane holds row (lane & 31) and columns 8*(v/4) + 4*(lane>>5) + v%4 of each tile.  The sub-tile
 // leaves through the wave's private LDS buffer `ep` (32 rows x 64 columns of fp32 at a time) and comes back with
 // lanes running along the rows, 8 consecutive columns per lane.  FULL: every element is inside the bounds.
+//
+// Key-norm maxima (EPI_QKV with g.kmax2, wave tiles of key columns that hold whole heads): on their way out the
+// lanes square and sum their 8 values, the lanes of a row are added per head in a fixed order, and one lane per row
+// accumulates the sums in the four spare floats at the end of the row's line in the staging buffer.  After the
+// last column group of a 32-row block, the largest row of each segment goes to kmax2[segment][head] (the sums are
+// >= 0, so their float bits order like unsigned integers).  The sums are taken before the rotary rotation (which
+// preserves the norm of every pair) and before rounding to bf16 (which changes a squared norm by less than 2^-7 of
+// itself): the factor 1.008 keeps the result an upper bound of the norm of the stored keys.
 template <int EPI, int MI, int NI, bool FULL>
 __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmArgs& g, float* ep, int64_t m_base, int wcol0,
                                               int lane, const TileBounds& tb) {
   constexpr int EPS = kEpStride;
   constexpr int TN = NI * 32;
   const int lr = lane & 31, lg = lane >> 5;
+  const bool kn = EPI == EPI_QKV && g.kmax2 != nullptr && wcol0 >= g.qcols && wcol0 < g.split;
   auto flush = [&](auto ngc, int mi, int nb, int64_t rbase) {
     constexpr int NGT = decltype(ngc)::value;
     constexpr int LPR = NGT * 4;                   // lanes per row (8 columns each)
@@ -95,8 +122,11 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
     float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
     if (EPI != EPI_PARTIAL && g.bias && col_ok) { b0 = *reinterpret_cast<const float4*>(g.bias + col); b1 = *reinterpret_cast<const float4*>(g.bias + col + 4); }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // plain stores read all staged values of the group first; the epilogues that keep other values in registers
+    // (old residual values, rotary factors, key-norm sums) read them pass by pass
+    constexpr bool BATCH = EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_GATED || EPI == EPI_PARTIAL;
     float4 v[NP][2];
-    if (EPI != EPI_RESID) {
+    if (BATCH) {
 #pragma unroll
       for (int ps = 0; ps < NP; ++ps) {
         const int r = ps * RPP + r0;
@@ -104,11 +134,39 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
         v[ps][1] = *reinterpret_cast<const float4*>(ep + r * EPS + c8 + 4);
       }
     }
+    if (EPI == EPI_QKV && kn) {
+      // this group's share of the squared key norms: per row, the lanes of the first head of the group and the
+      // lanes of the second (a group of 64 columns meets at most two heads of 64 or more columns)
+      const int h_first = (nb * 32) / g.kn_dh;
+      const bool second = (nb * 32 + c8) / g.kn_dh != h_first;
+#pragma unroll
+      for (int ps = 0; ps < NP; ++ps) {
+        const int r = ps * RPP + r0;
+        const int64_t row = rbase + r;
+        const bool ok = FULL || (row >= tb.row_lo && row < tb.row_hi && col_ok);
+        const float4 va = *reinterpret_cast<const float4*>(ep + r * EPS + c8), vb = *reinterpret_cast<const float4*>(ep + r * EPS + c8 + 4);
+        const float y[8] = {va.x + b0.x, va.y + b0.y, va.z + b0.z, va.w + b0.w, vb.x + b1.x, vb.y + b1.y, vb.z + b1.z, vb.w + b1.w};
+        float sq = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sq = fmaf(y[j], y[j], sq);
+        if (!ok) sq = 0.f;
+        float s0 = second ? 0.f : sq, s1 = second ? sq : 0.f;
+        // sums over the LPR (4 or 8) lanes of a row, in a fixed order; valid in the first lane of the row
+        s0 += lane_xor1(s0); s1 += lane_xor1(s1);
+        s0 += lane_xor2(s0); s1 += lane_xor2(s1);
+        if (LPR == 8) { s0 += lane_up4(s0); s1 += lane_up4(s1); }
+        if (lane % LPR == 0) {
+          float* acc2 = ep + r * EPS + 64 + h_first;
+          acc2[0] += s0;
+          if ((nb * 32 + NGT * 32 - 1) / g.kn_dh != h_first) acc2[1] += s1;
+        }
+      }
+    }
 #pragma unroll
     for (int ps = 0; ps < NP; ++ps) {
       const int64_t row = rbase + ps * RPP + r0;
       if (!FULL && (row < tb.row_lo || row >= tb.row_hi || !col_ok)) continue;
-      if (EPI == EPI_RESID) {                       // the old values hold the registers; read the staged sums pass by pass
+      if (!BATCH) {
         const int r = ps * RPP + r0;
         v[ps][0] = *reinterpret_cast<const float4*>(ep + r * EPS + c8);
         v[ps][1] = *reinterpret_cast<const float4*>(ep + r * EPS + c8 + 4);
@@ -178,6 +236,7 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int64_t rbase = m_base + mi * 32;
+    if (EPI == EPI_QKV && kn && lane < 32) *reinterpret_cast<float4*>(ep + lane * EPS + 64) = make_float4(0.f, 0.f, 0.f, 0.f);
     if (EPI == EPI_QKV && wcol0 + TN > g.split) {
       const int64_t row = rbase + lr;
       if (FULL || (row >= tb.row_lo && row < tb.row_hi)) {
@@ -203,6 +262,37 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
 #pragma unroll
     for (int nb = 0; nb + 2 <= NI; nb += 2) flush(std::integral_constant<int, 2>{}, mi, nb, rbase);
     if (NI & 1) flush(std::integral_constant<int, 1>{}, mi, NI - 1, rbase);
+    if (EPI == EPI_QKV && kn) {
+      // rows of this block -> table.  Lane l < 32 reads the sums of row l (up to four heads per wave tile).
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      const float4 sums = *reinterpret_cast<const float4*>(ep + lr * EPS + 64);
+      const float hs[4] = {sums.x, sums.y, sums.z, sums.w};
+      const int64_t row = rbase + lr;
+      const bool row_ok = FULL || (row >= tb.row_lo && row < tb.row_hi);
+      const int seg = row_ok ? g.row_seg[row] : -1;
+      const int seg_a = __builtin_amdgcn_readlane(seg, 0), seg_b = __builtin_amdgcn_readlane(seg, 31);
+      const bool one_segment = __all(row_ok) && seg_a == seg_b;        // rows are ordered by segment
+      const int head0 = (wcol0 - g.qcols) / g.kn_dh;
+      const int nh = TN / g.kn_dh;
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        if (h < nh) {
+          float vmax = hs[h] * 1.008f;
+          if (one_segment) {
+            // largest of the 32 rows (lanes 0..31): inside each row of 16 lanes, then lanes 0 and 16
+            vmax = fmaxf(vmax, lane_xor1(vmax));
+            vmax = fmaxf(vmax, lane_xor2(vmax));
+            vmax = fmaxf(vmax, lane_up4(vmax));
+            vmax = fmaxf(vmax, lane_up8(vmax));
+            const float top = fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 0)),
+                                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 16)));
+            if (lane == 0) table_max(g.kmax2 + (size_t)seg_a * g.kn_heads + head0 + h, __float_as_uint(top));
+          } else if (row_ok && lg == 0) {
+            table_max(g.kmax2 + (size_t)seg * g.kn_heads + head0 + h, __float_as_uint(vmax));
+          }
+        }
+      }
+    }
   }
 }
 
@@ -621,9 +711,20 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_bf16_persist_kernel(GemmA
       float* ep = reinterpret_cast<float*>(smem + (s_last ? STAGE : 0) + wave_u * EP_WAVE);
       const int64_t m_base = m0 + wm * TM;
       const int wcol0 = n0 + wn * TN;
-      const TileBounds tb{row_lo, g.m, col_lo, g.n, 0};
-      if (m0 == row_lo && n0 == col_lo) wave_epilogue<EPI, MI, NI, true>(acc, g, ep, m_base, wcol0, lane, tb);
-      else wave_epilogue<EPI, MI, NI, false>(acc, g, ep, m_base, wcol0, lane, tb);
+      // The epilogue reads its arguments (a dozen pointers and sizes that the k-loop never touches) from the kernel
+      // argument segment again, through a pointer the compiler cannot trace back: kept live across the k-loop they
+      // overflow the scalar registers and come back from scratch memory one dependent load at a time.
+      const __attribute__((address_space(4))) GemmArgs* ge =
+          (const __attribute__((address_space(4))) GemmArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+      asm volatile("" : "+s"(ge) : : "memory");
+      const GemmArgs& g2 = *(const GemmArgs*)ge;
+      // likewise the lane number: the epilogue's per-lane offsets are the same for every tile, and the compiler
+      // would compute them once before the first k-loop and carry them through it
+      int lane_e = lane;
+      asm volatile("" : "+v"(lane_e));
+      const TileBounds tb{row_lo, g2.m, col_lo, g2.n, 0};
+      if (m0 == row_lo && n0 == col_lo) wave_epilogue<EPI, MI, NI, true>(acc, g2, ep, m_base, wcol0, lane_e, tb);
+      else wave_epilogue<EPI, MI, NI, false>(acc, g2, ep, m_base, wcol0, lane_e, tb);
     }
     if (!has_next) break;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -671,17 +772,20 @@ static hipError_t launch_persist(const GemmArgs& a, hipStream_t s) {
 }
 
 
-hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
-  if (a.m == 0 || a.n == 0) return hipSuccess;
-  if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return hipErrorInvalidValue;
-  if (a.epi == EPI_QKV && (a.split % 8)) return hipErrorInvalidValue;
-  if (a.epi == EPI_QKV && a.rope && (a.rope_dh % 8 || a.rope_dh <= 0)) return hipErrorInvalidValue;
-  if (a.epi == EPI_GATED && (a.ldc % 4)) return hipErrorInvalidValue;
+namespace {
+enum GemmKernel { GK_INVALID, GK_P320, GK_P256, GK_SPLITK, GK_T64, GK_T128 };
+// which kernel a product runs on, and the width of its wave tiles
+GemmKernel choose_kernel(const GemmArgs& a, int* wave_tile_n, int* block_n) {
+  if (a.k <= 0 || a.k % 64 || a.lda % 8 || a.n <= 0 || a.n % 8 || a.ldc % 4) return GK_INVALID;
+  if (a.epi == EPI_QKV && (a.split % 8)) return GK_INVALID;
+  if (a.epi == EPI_QKV && a.rope && (a.rope_dh % 8 || a.rope_dh <= 0)) return GK_INVALID;
+  if (a.epi == EPI_GATED && (a.ldc % 4)) return GK_INVALID;
   // operand element offsets are kept in 32 bits
-  if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return hipErrorInvalidValue;
+  if ((double)a.m * (double)a.lda >= 4294967296.0 || (double)a.n * (double)a.k >= 4294967296.0) return GK_INVALID;
   // Persistent 256-row tiles (8 waves, one workgroup per CU) from about one and a half rounds of them over the 256
   // CUs.  A tile 320 columns wide is taken where it needs no more tile area x rounds than a 256-wide one (hidden
-  // sizes that are multiples of 320 but not of 256, such as 1280).  The kernel addresses its operands in bytes, 32 bits.
+  // sizes that are multiples of 320 but not of 256, such as 1280).  That kernel addresses its operands in bytes,
+  // 32 bits.
   const int64_t big_tiles = ((a.m + 255) / 256) * ((a.n + 255) / 256);
   if (big_tiles >= 400 && a.k >= 128 && a.m >= 256 && a.n >= 320 && a.epi != EPI_PARTIAL &&
       (double)a.m * (double)a.lda < 2147483648.0 && (double)a.n * (double)a.k < 2147483648.0) {
@@ -689,27 +793,59 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
       const int64_t t = ((a.m + bm - 1) / bm) * ((a.n + bn - 1) / bn);
       return ((t + 255) / 256) * bm * bn;
     };
-    if (area(256, 320) <= area(256, 256)) return launch_persist<256, 320, 4, 2>(a, s);
-    return launch_persist<256, 256, 2, 4>(a, s);
+    if (area(256, 320) <= area(256, 256)) { *wave_tile_n = 160; *block_n = 320; return GK_P320; }
+    *wave_tile_n = 64; *block_n = 256;
+    return GK_P256;
   }
   // a single small request: fewer than 200 tiles of 128x128 leave most CUs idle; 64x64 tiles
   // (2 waves) quadruple the number of workgroups
   const int64_t mid_tiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);
-  if (mid_tiles < 200 && a.epi == EPI_RESID && a.partial && a.k >= 2048 && (a.k / 64) % 4 == 0 && a.n % 8 == 0) {
-    // a long contraction over few rows (fc2 of one small request): 64x64 tiles would each walk all of k and
-    // re-read both operands from L2 twice as often; 128x128 tiles over a quarter of k each give as many
-    // workgroups with a quarter of the iterations.  The slices are added to C in a fixed order afterwards.
-    GemmArgs g = a;
-    g.epi = EPI_PARTIAL; g.ksplit = 4;
-    const hipError_t e = launch_cfg<128, 128, 2, 2, 64, 2, 2>(g, s);
-    if (e != hipSuccess) return e;
-    const int64_t n4 = (int64_t)a.m * (a.n / 4);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<float*>(a.c), a.ldc, a.partial, a.bias, a.m, a.n, 4);
-    return hipGetLastError();
+  *wave_tile_n = 64; *block_n = 128;
+  // a long contraction over few rows (fc2 of one small request): 64x64 tiles would each walk all of k and
+  // re-read both operands from L2 twice as often; 128x128 tiles over a quarter of k each give as many
+  // workgroups with a quarter of the iterations.  The slices are added to C in a fixed order afterwards.
+  if (mid_tiles < 200 && a.epi == EPI_RESID && a.partial && a.k >= 2048 && (a.k / 64) % 4 == 0) return GK_SPLITK;
+  if (mid_tiles < 200) { *wave_tile_n = 32; *block_n = 64; return GK_T64; }
+  return GK_T128;
+}
+}  // namespace
+
+bool gemm_bf16_can_fuse_key_norms(int64_t m, int n, int k, int qcols, int dh) {
+  if (dh != 64 && dh != 80) return false;
+  GemmArgs a{};
+  a.m = m; a.n = n; a.k = k; a.lda = k; a.ldc = 2 * qcols; a.epi = EPI_QKV; a.split = 2 * qcols; a.qcols = qcols;
+  int tn = 0, bn = 0;
+  const GemmKernel gk = choose_kernel(a, &tn, &bn);
+  if (gk == GK_INVALID || gk == GK_SPLITK) return false;
+  // whole heads per wave tile, wave tiles that start at head boundaries, no shifted last tile
+  return tn % dh == 0 && tn / dh <= 4 && qcols % tn == 0 && ((gk != GK_P320 && gk != GK_P256) || n % bn == 0);
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
+  if (a.m == 0 || a.n == 0) return hipSuccess;
+  int tn = 0, bn = 0;
+  const GemmKernel gk = choose_kernel(a, &tn, &bn);
+  if (a.epi == EPI_QKV && a.kmax2 &&
+      !(gk != GK_INVALID && (a.kn_dh == 64 || a.kn_dh == 80) && tn % a.kn_dh == 0 && a.qcols % tn == 0 &&
+        a.split == 2 * a.qcols && a.row_seg && ((gk != GK_P320 && gk != GK_P256) || a.n % bn == 0)))
+    return hipErrorInvalidValue;
+  switch (gk) {
+    case GK_P320: return launch_persist<256, 320, 4, 2>(a, s);
+    case GK_P256: return launch_persist<256, 256, 2, 4>(a, s);
+    case GK_SPLITK: {
+      GemmArgs g = a;
+      g.epi = EPI_PARTIAL; g.ksplit = 4;
+      const hipError_t e = launch_cfg<128, 128, 2, 2, 64, 2, 2>(g, s);
+      if (e != hipSuccess) return e;
+      const int64_t n4 = (int64_t)a.m * (a.n / 4);
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                         reinterpret_cast<float*>(a.c), a.ldc, a.partial, a.bias, a.m, a.n, 4);
+      return hipGetLastError();
+    }
+    case GK_T64: return launch_cfg<64, 64, 1, 2, 64, 2, 4>(a, s);
+    case GK_T128: return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
+    default: return hipErrorInvalidValue;
   }
-  if (mid_tiles < 200) return launch_cfg<64, 64, 1, 2, 64, 2, 4>(a, s);
-  return launch_cfg<128, 128, 2, 2, 64, 2, 2>(a, s);
 }
 
 }  // namespace tcmv

@@ -58,6 +58,9 @@ struct GemmArgs {
   const float* rope; int rope_dh;
   // EPI_QKV: columns below qcols (the queries) are multiplied by qscale before rounding (0 columns = off)
   int qcols; float qscale;
+  // EPI_QKV, optional (see gemm_bf16_can_fuse_key_norms): kmax2[row_seg[r]][h] = max(.., 1.008 * |k row r, head h|^2)
+  // over the key columns [qcols, split); kn_dh = head size, kn_heads = heads; float bits, table zeroed by the caller
+  uint32_t* kmax2; const int32_t* row_seg; int kn_dh; int kn_heads;
   // EPI_RESID with few rows and a long contraction (one small request): when `partial` is given (fp32,
   // room for 4 * m * n values) the launcher may cut k into 4 slices computed by 4 times as many workgroups
   // and add the slices to C in slice order in a second kernel (same result from run to run)
@@ -76,6 +79,8 @@ struct AttnArgs {
   int prescaled;                                 // bf16 path: the queries already carry the scale
   const uint32_t* kmax2;                         // bf16 path, may be null: [segments][heads] largest squared key norm (float bits)
   uint32_t* any_left;                            // with kmax2, may be null: zeroed word; set when a workgroup needs the reference-tracking copy
+  uint32_t* kmax_clear; int n_clear;             // with kmax2, may be null: n_clear words that the first kernel of the launch zeroes
+                                                 // (the key-norm block of the next layer)
 };
 
 struct PreprocArgs {
@@ -98,6 +103,9 @@ bool preprocess_has_strip_kernel(int patch, int tpatch);
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d,
                             float eps, int out_bf16, hipStream_t s, int rms = 0);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+// true when launch_gemm_bf16 computes the key-norm maxima in the epilogue of an m x n x k QKV projection whose key
+// columns are [qcols, 2 qcols) with heads of dh columns (the wave tiles must line up with the heads)
+bool gemm_bf16_can_fuse_key_norms(int64_t m, int n, int k, int qcols, int dh);
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s);
 // windowed layers whose windows hold at most 64 tokens: every work item is one whole window (bf16, prescaled queries)
@@ -112,6 +120,10 @@ hipError_t launch_knorm(const void* k, int64_t ldk, int64_t rows, int heads, int
                         uint32_t* kmax2, hipStream_t s);
 // zero fill of a 16-byte aligned region whose size is a multiple of 16
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// start of an encode on the bf16 path: zeroes the columns [pads[2i], pads[2i+1]) of every row of vt [rows, ldvt]
+// (bf16) and n_words 32-bit words at `words`
+hipError_t launch_attn_prepare(void* vt, int64_t ldvt, int rows, const int32_t* pads, int n_pads, uint32_t* words,
+                               int n_words, hipStream_t s);
 // hidden[cls_rows[i]] = cls + pos0[0] (if pos0)
 hipError_t launch_cls_rows(float* hidden, const int32_t* cls_rows, int n, const float* cls,
                            const float* pos0, int d, hipStream_t s);

@@ -30,6 +30,12 @@ class Plan:
         self.handle = B.tcmv_plan_create(enc.ctx, items)
         self.info = B.tcmv_plan_query(self.handle)
         self.cu_seqlens = B.tcmv_plan_cu_seqlens(self.handle, self.n_items)
+        # device copy of the plan's index metadata: memory from PyTorch, copy enqueued by the library on the
+        # current stream (stage calls on other streams must be ordered after it, see run_pipelined)
+        self.meta = None
+        if frame_tensors and self.info.meta_bytes:
+            self.meta = torch.empty(int(self.info.meta_bytes), dtype=torch.uint8, device=enc.device)
+            B.tcmv_plan_upload(enc.ctx, self.handle, self.meta, self.meta.numel(), _stream_ptr())
 
     def row_map(self, which):
         return B.tcmv_plan_row_map(self.handle, which)
@@ -164,7 +170,7 @@ class VisionEncoder:
         if out is None:
             out = torch.empty((i.n_patch_rows, i.k_pad), dtype=torch.bfloat16 if self.bf16 else torch.float32,
                               device=self.device)
-        B.tcmv_preprocess(self.ctx, plan.handle, out, _stream_ptr())
+        B.tcmv_preprocess(self.ctx, plan.handle, plan.meta, out, _stream_ptr())
         return out
 
     def workspace(self, nbytes: int) -> torch.Tensor:
@@ -178,7 +184,7 @@ class VisionEncoder:
             hidden = torch.empty((i.n_tokens, self.desc.d), dtype=torch.float32, device=self.device)
         if workspace is None:
             workspace = self.workspace(i.encode_workspace_bytes)
-        B.tcmv_encode(self.ctx, plan.handle, patches, hidden, workspace, workspace.numel(), _stream_ptr())
+        B.tcmv_encode(self.ctx, plan.handle, plan.meta, patches, hidden, workspace, workspace.numel(), _stream_ptr())
         return hidden
 
     def merge_project(self, plan: Plan, hidden: torch.Tensor, out: Optional[torch.Tensor] = None,

@@ -157,9 +157,64 @@ def test_device_calls_fail_cleanly_without_weights_or_gpu():
     desc = workloads.qwen_like_desc(layers=1, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
     enc = VisionEncoder(desc)
     pl = enc.plan([workloads.Item(1, 1, 28, 28, 28, 28)], upload=False)
-    rc = B.lib().tcmv_encode(enc.ctx, pl.handle, 256, 256, 256, 1 << 30, None)
+    rc = B.lib().tcmv_encode(enc.ctx, pl.handle, 256, 256, 256, 256, 1 << 30, None)
     assert rc == B.TCMV_E_NO_WEIGHTS
-    rc = B.lib().tcmv_preprocess(enc.ctx, pl.handle, 256, None)     # item has a null frame pointer
+    rc = B.lib().tcmv_preprocess(enc.ctx, pl.handle, 256, 256, None)     # item has a null frame pointer
     assert rc == B.TCMV_E_INVALID_ARG
     assert "frame pointer" in B.tcmv_last_error(enc.ctx)
     assert B.tcmv_op_attention_workspace(B.TCMV_BF16, [0, 100, 100, 164], 128, 2) > 0
+
+
+def test_plan_metadata_belongs_to_the_caller():
+    """The library hands out the plan's index metadata as host bytes and never allocates device memory itself: the
+    stage calls take the caller's device copy, and refuse a missing, misaligned or short one."""
+    desc = workloads.qwen_like_desc(layers=1, d=320, heads=4, mlp=640, out_dim=192, max_grid=16)
+    enc = VisionEncoder(desc)
+    item = workloads.Item(1, 1, 28, 28, 28, 28)
+    pl = enc.plan([item], upload=False)
+    assert pl.meta is None and pl.info.meta_bytes > 0 and pl.info.meta_bytes % 256 == 0
+    blob = B.tcmv_plan_meta(pl.handle)
+    assert len(blob) == pl.info.meta_bytes
+    # the normalisation table (3 x 256 values, bf16-representable for a bf16 model) is part of it
+    tab = np.array([((v / 255.0) - 0.5) / 0.5 for v in range(256)], np.float32)
+    tab = (tab.view(np.uint32) + 0x7FFF + ((tab.view(np.uint32) >> 16) & 1) & 0xFFFF0000).astype(np.uint32).view(np.float32)
+    assert blob.find(tab.tobytes()) >= 0
+    # an empty plan needs no metadata
+    empty = enc.plan([workloads.Item(0, 0, 0, 0, 0, 0)], upload=False)
+    assert empty.info.meta_bytes == 0 and B.tcmv_plan_meta(empty.handle) == b""
+    assert B.lib().tcmv_plan_upload(empty.handle, None, 0, None) == B.TCMV_OK
+    # argument checks come before any device work
+    assert B.lib().tcmv_plan_upload(pl.handle, None, pl.info.meta_bytes, None) == B.TCMV_E_INVALID_ARG
+    assert B.lib().tcmv_plan_upload(pl.handle, 256 + 16, pl.info.meta_bytes, None) == B.TCMV_E_INVALID_ARG
+    assert B.lib().tcmv_plan_upload(pl.handle, 256, pl.info.meta_bytes - 1, None) == B.TCMV_E_WORKSPACE_TOO_SMALL
+    assert B.lib().tcmv_plan_upload(None, 256, 0, None) == B.TCMV_E_INVALID_ARG
+    rc = B.lib().tcmv_preprocess(enc.ctx, pl.handle, None, 256, None)
+    assert rc == B.TCMV_E_INVALID_ARG
+
+
+def test_attention_index_is_host_data():
+    cu = [0, 100, 100, 164]
+    n = B.lib().tcmv_op_attention_index_bytes(B.TCMV_BF16, (C.c_int64 * 4)(*cu), 3, 128, 2)
+    assert n > 0 and n % 256 == 0
+    idx = B.tcmv_op_attention_index(B.TCMV_BF16, cu, 128, 2)
+    assert len(idx) == n
+    vcol = np.frombuffer(idx[:164 * 4], np.int32)
+    # every row has its own column in the transposed-V buffer; the second non-empty segment starts at a multiple of 64
+    assert len(set(vcol.tolist())) == 164 and vcol[:100].max() < 128 and vcol[100:].min() == 128
+    buf = C.create_string_buffer(16)
+    assert B.lib().tcmv_op_attention_index(B.TCMV_BF16, (C.c_int64 * 4)(*cu), 3, 128, 2, buf, 16) == B.TCMV_E_WORKSPACE_TOO_SMALL
+    assert B.lib().tcmv_op_attention_index_bytes(B.TCMV_BF16, (C.c_int64 * 4)(0, 5, 3, 9), 3, 128, 2) == 0
+
+
+def test_windowed_plan_whose_transposed_values_do_not_fit_32_bit_offsets_is_refused():
+    """Every window is padded to 64 columns of the transposed values, so a plan with small windows needs far more
+    columns than it has tokens; the offset guard must count them."""
+    desc = workloads.ModelDesc(dtype="bf16", layers=1, d=2048, heads=32, mlp=2048, patch=14, tpatch=1, merge=1,
+                               pos="none", window=2, full_every=0)
+    enc = VisionEncoder(desc)
+    # 8 x 8 grids: 16 windows of 4 tokens -> 1024 columns for 64 tokens
+    items = [workloads.Item(1, 1, 112, 112, 112, 112)] * 3000
+    with pytest.raises(B.TcmvError) as e:
+        enc.plan(items, upload=False)
+    assert e.value.code == B.TCMV_E_BAD_SHAPE and "transposed" in str(e.value)
+    assert enc.plan(items[:1500], upload=False).info.n_tokens == 1500 * 64

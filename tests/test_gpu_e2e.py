@@ -136,7 +136,7 @@ def test_workspace_too_small_and_missing_projector_are_reported():
     small = enc.workspace(256)
     hidden = torch.empty((pl.info.n_tokens, wl.desc.d), device="cuda:0")
     with pytest.raises(B.TcmvError) as e:
-        B.tcmv_encode(enc.ctx, pl.handle, patches, hidden, small, small.numel())
+        B.tcmv_encode(enc.ctx, pl.handle, pl.meta, patches, hidden, small, small.numel())
     assert e.value.code == B.TCMV_E_WORKSPACE_TOO_SMALL
     with pytest.raises(B.TcmvError) as e:
         B.tcmv_merge_project(enc.ctx, pl.handle, hidden, hidden, small, small.numel())

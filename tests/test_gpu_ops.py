@@ -123,8 +123,9 @@ def _attn(dtype, qkv, cu, d, heads):
     ws_bytes = B.tcmv_op_attention_workspace(cd, cu, d, heads)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
     ws.fill_(0xFF)                                   # poison: padding must never be used
+    index = torch.frombuffer(bytearray(B.tcmv_op_attention_index(cd, cu, d, heads)), dtype=torch.uint8).to(DEV)
     out = torch.full((T, d), float("nan"), dtype=tdt, device=DEV)
-    B.tcmv_op_attention(cd, dev(qkv, tdt), cu, d, heads, out, ws, ws.numel())
+    B.tcmv_op_attention(cd, dev(qkv, tdt), cu, d, heads, index, out, ws, ws.numel())
     sync()
     return out.float().cpu().numpy()
 
@@ -224,7 +225,7 @@ def test_attention_zero_queries_give_mean_of_values():
 def test_empty_inputs_are_no_ops():
     B.tcmv_op_layernorm(B.TCMV_BF16, None, None, None, None, 0, 256, 1e-6)
     B.tcmv_op_gemm(B.TCMV_BF16, 0, None, None, None, None, 0, 128, 64)
-    B.tcmv_op_attention(B.TCMV_BF16, None, [0, 0, 0], 128, 2, None, None, 0)
+    B.tcmv_op_attention(B.TCMV_BF16, None, [0, 0, 0], 128, 2, None, None, None, 0)
     sync()
 
 
