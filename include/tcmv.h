@@ -302,6 +302,18 @@ int tcmv_op_attention_index(int dtype, const int64_t *cu_seqlens, int n_seg, int
 int tcmv_op_attention(int dtype, const void *d_qkv, const int64_t *cu_seqlens, int n_seg, int d, int heads,
                       const void *d_index, void *d_out, void *d_workspace, size_t workspace_bytes, void *stream);
 
+/* tcmv_op_attention for callers that cannot allocate device memory (code under HIP
+ * graph capture, serving loops and harnesses that forbid hipMalloc): same arguments
+ * and same result, but no workspace argument.  The scratch lives in a fixed array of
+ * TCMV_NOALLOC_SCRATCH_BYTES in device memory that every GPU the library runs on
+ * holds until the process ends; the call allocates and frees nothing.  Shapes whose
+ * scratch (tcmv_op_attention_workspace) exceeds that size return
+ * TCMV_E_WORKSPACE_TOO_SMALL.  All calls on one GPU share the array: calls that
+ * overlap on one GPU (two streams, two threads) race; calls on one stream do not. */
+#define TCMV_NOALLOC_SCRATCH_BYTES (16u << 20)
+int tcmv_op_attention_noalloc(int dtype, const void *d_qkv, const int64_t *cu_seqlens, int n_seg, int d, int heads,
+                              const void *d_index, void *d_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -89,7 +89,10 @@ SIGNATURES = {
                                           C.c_size_t]),
     "tcmv_op_attention": (C.c_int, [C.c_int, C.c_void_p, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tcmv_op_attention_noalloc": (C.c_int, [C.c_int, C.c_void_p, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]),
 }
+TCMV_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 _lib = None
 
@@ -300,3 +303,10 @@ def tcmv_op_attention(dtype, d_qkv, cu_seqlens, d, heads, d_index, d_out, d_work
     if rc != TCMV_OK:
         raise TcmvError(rc, "tcmv_op_attention")
 
+
+def tcmv_op_attention_noalloc(dtype, d_qkv, cu_seqlens, d, heads, d_index, d_out, stream=None):
+    n = len(cu_seqlens) - 1
+    arr = (C.c_int64 * (n + 1))(*cu_seqlens)
+    rc = lib().tcmv_op_attention_noalloc(dtype, _ptr(d_qkv), arr, n, d, heads, _ptr(d_index), _ptr(d_out), stream)
+    if rc != TCMV_OK:
+        raise TcmvError(rc, "tcmv_op_attention_noalloc")

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -979,6 +980,42 @@ int tcmv_op_attention_index(int dtype, const int64_t* cu_seqlens, int n_seg, int
   if (!work.empty()) std::memcpy(h + L.work, work.data(), work.size() * sizeof(AttnWork));
   if (!rseg.empty()) std::memcpy(h + L.rseg, rseg.data(), rseg.size() * 4);
   return TCMV_OK;
+}
+
+// ---- the attention operator for callers that cannot allocate: its scratch is a fixed array in device memory ----
+namespace {
+static __device__ __align__(256) unsigned char scratch[TCMV_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+uint8_t* g_scratch_ptr[kMaxDevices] = {};          // device address of each GPU's own copy of `scratch`
+std::mutex g_scratch_mu;
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+int scratch_of_current_device(uint8_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TCMV_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TCMV_E_HIP;
+    g_scratch_ptr[dev] = reinterpret_cast<uint8_t*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return TCMV_OK;
+}
+}  // namespace
+
+int tcmv_op_attention_noalloc(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads,
+                              const void* d_index, void* d_out, void* stream) {
+  OpAttnLayout L{};
+  const int rc = op_attention_check(dtype, d_qkv, cu_seqlens, n_seg, d, heads, d_index, d_out, &L);
+  if (rc != TCMV_OK || L.T == 0) return rc;
+  if (L.ws_total > (size_t)TCMV_NOALLOC_SCRATCH_BYTES) return TCMV_E_WORKSPACE_TOO_SMALL;   // beyond the fixed scratch
+  uint8_t* ptr = nullptr;
+  const int rs = scratch_of_current_device(&ptr);
+  if (rs != TCMV_OK) return rs;
+  // the kernels zero-fill what they read before writing it (transposed-V padding, key-norm table): the array keeps
+  // the previous call's contents
+  return op_attention_run(dtype, d_qkv, d, heads, L, d_index, d_out, ptr, (hipStream_t)stream);
 }
 
 int tcmv_op_attention(int dtype, const void* d_qkv, const int64_t* cu_seqlens, int n_seg, int d, int heads,
