@@ -2,20 +2,20 @@
  * tcms.h - C ABI of the scheduling front-end that decides in which order requests
  * enter the vision encoder (host code only; part of libtcmv.so).
  *
- * It follows the components of the paper's Section 4 (Fig. 6):
- *   Impact Estimator   (Sec. 4.3)  tcms_fit_linear, tcms_fit_quantile, tcms_pinball_loss
- *   Request Classifier (Sec. 4.4)  tcms_classify_naive, tcms_cluster_fit, tcms_cluster_assign
- *   Queue Manager      (Sec. 4.5)  tcms_queues_*
- *   Priority Regulator (Sec. 4.6)  tcms_priority, tcms_score, tcms_regulator_default
+ * It follows the components of the paper's Section 3 (Fig. 5):
+ *   Impact Estimator   (Sec. 3.3)  tcms_fit_linear, tcms_fit_quantile, tcms_pinball_loss
+ *   Request Classifier (Sec. 3.4)  tcms_classify_naive, tcms_cluster_fit, tcms_cluster_assign
+ *   Queue Manager      (Sec. 3.5)  tcms_queues_*
+ *   Priority Regulator (Sec. 3.6)  tcms_priority, tcms_score, tcms_regulator_default
  *   and a trace-driven model of one non-preemptive server, tcms_simulate, to compare the
- *   policies the paper compares in Sec. 4.4 / 4.6 (FCFS, static priority, regulated).
+ *   policies the paper compares in Sec. 3.4 / 3.6 (FCFS, static priority, regulated).
  *
  * All pointers are HOST pointers owned by the caller unless stated otherwise; arrays
  * are contiguous.  Functions return TCMS_OK (0) or a negative TCMS_E_* code and write
  * nothing to their outputs on error.  Nothing here touches the GPU.  Functions are
  * re-entrant; a tcms_queues object must not be used from two threads at once.
  *
- * Classes (Sec. 3.2, the trucks / cars / motorcycles abstraction): the smaller the code,
+ * Classes (Sec. 3.1, the trucks / cars / motorcycles abstraction): the smaller the code,
  * the lighter the request.
  */
 #ifndef TCMS_H
@@ -31,7 +31,7 @@ enum { TCMS_MOTORCYCLE = 0, TCMS_CAR = 1, TCMS_TRUCK = 2 };
 enum { TCMS_FCFS = 0, TCMS_STATIC = 1, TCMS_REGULATED = 2 };
 enum { TCMS_OK = 0, TCMS_E_INVALID_ARG = -1, TCMS_E_EMPTY = -2, TCMS_E_DEGENERATE = -3 };
 
-/* ---- Impact Estimator (Sec. 4.3) -------------------------------------------------------
+/* ---- Impact Estimator (Sec. 3.3) -------------------------------------------------------
  * The paper predicts a request's cost from its size with a linear regression for text and
  * with a quantile regression at the 90th percentile for image and video requests, so that
  * heavy requests are not underestimated. */
@@ -52,7 +52,7 @@ double tcms_pinball_loss(const double* x, const double* y, int64_t n, double q, 
 int tcms_fit_quantile(const double* x, const double* y, int64_t n, double q, double* slope, double* intercept,
                       double* loss);
 
-/* ---- Request Classifier (Sec. 4.4) ----------------------------------------------------- */
+/* ---- Request Classifier (Sec. 3.4) ----------------------------------------------------- */
 
 /* The paper's "naive" rule: modality 0 text -> motorcycle, 1 image -> car, 2 video -> truck;
  * TCMS_E_INVALID_ARG otherwise. */
@@ -74,17 +74,17 @@ int tcms_cluster_fit(const double* features, int64_t n, int max_iter, tcms_clust
 /* Class (0..2) of one request; negative code on invalid input. */
 int tcms_cluster_assign(const tcms_cluster_model* m, double time, double tokens);
 
-/* ---- Priority Regulator (Sec. 4.6) ------------------------------------------------------
+/* ---- Priority Regulator (Sec. 3.6) ------------------------------------------------------
  * Priority_c = static_priority[c] + (1 - exp(-k[c] * wait^p[c])),  Score_c = -log(Priority_c);
  * the request with the lowest score is served next.  Score is +infinity when Priority is 0. */
 typedef struct { double static_priority[3], k[3], p[3]; } tcms_regulator;
 
-/* The constants of the paper's evaluation (Sec. 6.1, "Configuration"). */
+/* The constants of the paper's evaluation (Sec. 4.1, "Configuration"). */
 void tcms_regulator_default(tcms_regulator* r);
 double tcms_priority(const tcms_regulator* r, int cls, double wait);
 double tcms_score(const tcms_regulator* r, int cls, double wait);
 
-/* ---- Queue Manager (Sec. 4.5) -----------------------------------------------------------
+/* ---- Queue Manager (Sec. 3.5) -----------------------------------------------------------
  * Three FCFS queues, one per class.  pop returns the request to serve next at time `now`:
  *   TCMS_FCFS       earliest arrival over all queues,
  *   TCMS_STATIC     head of the lightest non-empty class,

@@ -9,7 +9,7 @@ arithmetic for it; the readings implemented here are:
              11-bit fractional weights, one rounding at the end;
   normalise  x = (v/255 - mean_c)/std_c evaluated in double, rounded once to
              fp32 and, for bf16 models, once more to bf16 (ties to even);
-  patchify   the "grid of patches with standardized dimensions" of Sec. 2.2:
+  patchify   Sec. 2.2 has the image cut into a grid of equally sized patches:
              frames are taken in groups of `tpatch` (a still image is repeated
              `tpatch` times); tokens are ordered (t, h, w) for merge=1 and
              (t, h//2, w//2, h%2, w%2) for merge=2 so that each 2x2 merge group

@@ -1,16 +1,16 @@
 """CPU reference for the scheduling front-end (TEST INFRASTRUCTURE ONLY).
 
-The paper's components, in the order a request meets them (Sec. 4, Fig. 6):
+The paper's components, in the order a request meets them (Sec. 3, Fig. 5):
 
-  Impact Estimator   (Sec. 4.3)  cost of a request from its size: ordinary least squares
+  Impact Estimator   (Sec. 3.3)  cost of a request from its size: ordinary least squares
                                  for text, quantile regression at the 90th percentile for
                                  image / video requests
-  Request Classifier (Sec. 4.4)  "naive": modality -> class; "smart": a clustering model
+  Request Classifier (Sec. 3.4)  "naive": modality -> class; "smart": a clustering model
                                  with three clusters on the estimator's two outputs
-  Queue Manager      (Sec. 4.5)  one FCFS queue per class
-  Priority Regulator (Sec. 4.6)  Priority_c = Static_c + (1 - exp(-k_c * wait^p_c)),
+  Queue Manager      (Sec. 3.5)  one FCFS queue per class
+  Priority Regulator (Sec. 3.6)  Priority_c = Static_c + (1 - exp(-k_c * wait^p_c)),
                                  Score_c = -log(Priority_c), lowest score is served next;
-                                 constants of Sec. 6.1 ("Configuration")
+                                 constants of Sec. 4.1 ("Configuration")
 
 Each function is the definition written out: least squares in closed form, the
 quantile regression as the linear program it is defined by (solved by
@@ -49,11 +49,11 @@ from scipy.optimize import linprog
 MOTORCYCLE, CAR, TRUCK = 0, 1, 2
 FCFS, STATIC, REGULATED = 0, 1, 2
 
-# Sec. 6.1, "Configuration": StaticPriority, k and p for motorcycles, cars, trucks
+# Sec. 4.1, "Configuration": StaticPriority, k and p for motorcycles, cars, trucks
 PAPER_REGULATOR = {"static": (0.1, 0.05, 0.0), "k": (0.05, 0.003, 0.00075), "p": (3.5, 2.5, 1.1)}
 
 
-# ---- Impact Estimator (Sec. 4.3) ----------------------------------------------------------
+# ---- Impact Estimator (Sec. 3.3) ----------------------------------------------------------
 def fit_linear(x, y):
     """Least squares line y ~ intercept + slope * x; returns (slope, intercept)."""
     x = np.asarray(x, np.float64)
@@ -91,7 +91,7 @@ def fit_quantile(x, y, q):
     return slope, intercept, pinball_loss(x, y, q, slope, intercept)
 
 
-# ---- Request Classifier (Sec. 4.4) --------------------------------------------------------
+# ---- Request Classifier (Sec. 3.4) --------------------------------------------------------
 def classify_naive(modality: int) -> int:
     """text -> motorcycle, image -> car, video -> truck (modality codes 0, 1, 2)."""
     return {0: MOTORCYCLE, 1: CAR, 2: TRUCK}[int(modality)]
@@ -132,7 +132,7 @@ def cluster_assign(model, time, tokens) -> int:
     return int(np.argmin(((model["centroid"] - z) ** 2).sum(axis=1)))
 
 
-# ---- Priority Regulator (Sec. 4.6) --------------------------------------------------------
+# ---- Priority Regulator (Sec. 3.6) --------------------------------------------------------
 def priority(cls: int, wait: float, reg=PAPER_REGULATOR) -> float:
     return reg["static"][cls] + (1.0 - math.exp(-reg["k"][cls] * wait ** reg["p"][cls]))
 
@@ -142,7 +142,7 @@ def score(cls: int, wait: float, reg=PAPER_REGULATOR) -> float:
     return math.inf if pr <= 0.0 else -math.log(pr)
 
 
-# ---- Queue Manager + one server (Sec. 4.5) -------------------------------------------------
+# ---- Queue Manager + one server (Sec. 3.5) -------------------------------------------------
 def simulate(policy: int, arrival: Sequence[float], service: Sequence[float], cls: Sequence[int],
              reg=PAPER_REGULATOR):
     """One non-preemptive server.  Requests (sorted by arrival time) wait in the queue of

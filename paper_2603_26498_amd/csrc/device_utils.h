@@ -32,7 +32,7 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 // GELU for bf16 outputs: gelu(x) = max(x, 0) - |x| * Phi(-|x|), with the lower tail of the normal distribution
 // evaluated as 2^G(|x|), G a polynomial of degree 5 fitted to log2 Phi(-a) on [0, 5.5] (|error| <= 3.6e-4, so the
 // tail is accurate in RELATIVE terms: 2.5e-4).  Beyond 5.5 the argument of G is held: the result is then off by at
-// most |x| * Phi(-5.5) < 2e-7 * |x| / 10.  Absolute error of the product <= 3.5e-5; after rounding to bf16 the
+// most |x| * Phi(-5.5) < 2e-8 * |x|.  Absolute error of the product <= 3.5e-5; after rounding to bf16 the
 // result is within one bf16 unit in the last place of the rounded exact value (or within 2^-22 of it where that is
 // larger), for every x in [-10, 10].  5 fused multiply-adds, one exp2 and three other vector instructions.
 __device__ __forceinline__ float gelu_bf16(float x) {

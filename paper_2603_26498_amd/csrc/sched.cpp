@@ -1,5 +1,5 @@
 // Scheduling front-end (host code): Impact Estimator fits, Request Classifiers, Priority
-// Regulator, Queue Manager and a one-server trace model, after Sections 4.3 - 4.6 of the
+// Regulator, Queue Manager and a one-server trace model, after Sections 3.3 - 3.6 of the
 // paper.  See tcms.h for the contract of every entry point.
 #include "../../include/tcms.h"
 

@@ -1,12 +1,12 @@
 """Workload Profiler and Impact Estimator on this library's own encoder, and a policy
 comparison on a synthetic arrival trace.
 
-The paper's Workload Profiler (Sec. 4.2) runs requests of increasing size one at a time and
+The paper's Workload Profiler (Sec. 3.2) runs requests of increasing size one at a time and
 records, per request, the preprocessing time, the encoder time and the number of tokens; the
-Impact Estimator (Sec. 4.3) fits simple per-modality models on those records (a linear
+Impact Estimator (Sec. 3.3) fits simple per-modality models on those records (a linear
 regression, and a quantile regression at the 90th percentile for image and video requests)
-and reports the prediction error (Fig. 9).  The Request Classifier (Sec. 4.4), the Queue
-Manager and the Priority Regulator (Sec. 4.5, 4.6) then order the requests.
+and reports the prediction error (Fig. 7).  The Request Classifier (Sec. 3.4), the Queue
+Manager and the Priority Regulator (Sec. 3.5, 3.6) then order the requests.
 
 Everything measured here runs through libtcmv.so: the GPU kernels for the records, the C++
 front-end (include/tcms.h) for fits, classification and the one-server trace model.  Inputs
@@ -120,7 +120,7 @@ def estimator_report(models, recs):
 
 
 def make_trace(rng, n, rate, mix=(200, 24, 2)):
-    """Poisson arrivals (Sec. 6.1: request arrivals follow a Poisson distribution); modality drawn with the
+    """Arrivals are a Poisson process, as in the evaluation set-up of Sec. 4.1; modality drawn with the
     proportions text : image : video = mix; sizes as in the mixed workload (images 28*{8..48} per side,
     videos of 8..64 frames at 448x448)."""
     p = np.asarray(mix, float) / sum(mix)
@@ -136,7 +136,7 @@ def make_trace(rng, n, rate, mix=(200, 24, 2)):
 
 
 def fit_classifier(models, recs, n_text=16):
-    """The clustering classifier is trained on profiling data (Sec. 4.4): the estimator's outputs for the
+    """The clustering classifier is trained on profiling data (Sec. 3.4): the estimator's outputs for the
     profiled requests, plus text requests, which need no work from the vision stages."""
     feats = [(predict(models, r["modality"], r["tokens"]), float(r["tokens"])) for r in recs if r["modality"] != TEXT]
     feats += [(0.0, 0.0)] * n_text

@@ -3,7 +3,7 @@ front-end deciding which requests enter the next encoder batch.
 
 This joins the pieces: the Impact Estimator's fitted lines give every arriving request an
 estimated stage time, the Request Classifier puts it into one of the three queues, and each
-time the GPU is free the Queue Manager / Priority Regulator (Sec. 4.5, 4.6) hand out requests
+time the GPU is free the Queue Manager / Priority Regulator (Sec. 3.5, 3.6) hand out requests
 until a token budget is filled; the batch then runs preprocess + encode + merge/project as one
 plan.  Text requests need nothing from the vision stages and leave as soon as they are
 scheduled.  Measured per request: waiting time (arrival -> start of its batch) and time in the

@@ -223,7 +223,7 @@ def test_token_counts_of_the_workloads():
 
 
 def test_video_as_frames_shares_patch_halves_with_the_video():
-    """Feeding a video frame by frame (Sec. 7.1) repeats every frame over the
+    """Feeding a video frame by frame (Sec. 4.1, "Models") repeats every frame over the
     temporal patch; the video pairs consecutive frames.  So row r of the video's
     frame pair j holds, in its first temporal slot, what image 2j holds there, and
     in its second slot what image 2j+1 holds there."""

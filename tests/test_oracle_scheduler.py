@@ -64,7 +64,7 @@ def test_quantile_regression_residual_counts_and_constant_x():
         r = y - (i + s * x)
         tol = 1e-7
         assert (r < -tol).sum() <= q * len(x) + 1e-9 <= (r <= tol).sum() + 1e-9
-    # P90 line lies above the least-squares line over the data range: it must not underestimate (Sec. 4.3)
+    # P90 line lies above the least-squares line over the data range: it must not underestimate (Sec. 3.3)
     s9, i9, _ = S.fit_quantile(x, y, 0.9)
     sl, il = S.fit_linear(x, y)
     assert i9 + s9 * x.mean() > il + sl * x.mean()
@@ -108,7 +108,7 @@ def test_clustering_recovers_separated_groups_and_matches_the_best_partition():
 
 
 def test_long_text_and_short_video_can_change_class():
-    """Sec. 4.4: resource-aware features let a very long text leave the motorcycles and a short video join
+    """Sec. 3.4: resource-aware features let a very long text leave the motorcycles and a short video join
     the cars, which the modality rule cannot do."""
     rng = np.random.default_rng(4)
     feats = np.concatenate([np.c_[rng.uniform(1, 4, 40), rng.uniform(20, 200, 40)],
@@ -147,7 +147,7 @@ def test_regulator_closed_forms():
 
 
 def test_regulator_ordering_described_by_the_paper():
-    """Sec. 4.6: motorcycles gain priority rapidly, cars gradually, trucks very slowly; the waits at which the
+    """Sec. 3.6: motorcycles gain priority rapidly, cars gradually, trucks very slowly; the waits at which the
     age term reaches one half are about 2 s, 9 s and 8 minutes."""
     half = [(math.log(2.0) / S.PAPER_REGULATOR["k"][c]) ** (1.0 / S.PAPER_REGULATOR["p"][c]) for c in range(3)]
     assert 2.0 < half[0] < 2.3 and 8.5 < half[1] < 9.0 and 480 < half[2] < 520

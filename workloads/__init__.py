@@ -236,7 +236,7 @@ def config5(n_videos=2, n_images=24, n_text=200, video_frames=32, video_side=448
 
 def config6(n_frames=64, side=448, layers=32, with_frames=True, desc=None) -> Workload:
     """The frames of the config-4 video submitted as a sequence of still images
-    (Sec. 7.1 notes that some models treat a video that way): one request and one
+    (Sec. 4.1, "Models", notes that some models treat a video that way): one request and one
     attention segment per frame, each frame repeated to fill the temporal patch.
     Same pixels and same encoder as config 4, twice the tokens, attention confined
     to 1024-token segments."""
