@@ -52,6 +52,20 @@ double tcms_pinball_loss(const double* x, const double* y, int64_t n, double q, 
 int tcms_fit_quantile(const double* x, const double* y, int64_t n, double q, double* slope, double* intercept,
                       double* loss);
 
+/* The same two fits with a second regressor, y ~ coef[0] + coef[1]*x1 + coef[2]*x2.  It is meant for
+ * x1 = tokens of a request and x2 = sum of its squared attention-segment lengths: the attention
+ * work of the vision encoder grows with x2, everything else with x1, so this is the smallest model
+ * that follows both short images and long videos.  coef: 3 doubles, written by the call.
+ * tcms_fit_linear2: a constant regressor gets coefficient 0; proportional regressors share the slope
+ * (minimum-norm solution of the centred, scaled problem).  tcms_fit_quantile2: exact (the optimum is
+ * a plane through three data points; for every pair of points the best plane through both is a
+ * weighted quantile), O(n^3 log n) time, n <= 4096; the minimum is unique, the plane need not be. */
+int tcms_fit_linear2(const double* x1, const double* x2, const double* y, int64_t n, double* coef);
+double tcms_pinball_loss2(const double* x1, const double* x2, const double* y, int64_t n, double q,
+                          const double* coef);
+int tcms_fit_quantile2(const double* x1, const double* x2, const double* y, int64_t n, double q, double* coef,
+                       double* loss);
+
 /* ---- Request Classifier (Sec. 3.4) ----------------------------------------------------- */
 
 /* The paper's "naive" rule: modality 0 text -> motorcycle, 1 image -> car, 2 video -> truck;

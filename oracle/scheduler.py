@@ -91,6 +91,50 @@ def fit_quantile(x, y, q):
     return slope, intercept, pinball_loss(x, y, q, slope, intercept)
 
 
+def fit_linear2(x1, x2, y):
+    """Least squares plane y ~ c0 + c1*x1 + c2*x2; returns (c0, c1, c2).  The second regressor is meant for the
+    sum of squared attention-segment lengths of a request: the encoder's attention work grows with it while the
+    rest grows with the token count, so a model that is "simple" in the sense of Sec. 3.3 but has both terms
+    follows long videos where a line in the token count cannot.  Regressors that carry no information of their own
+    (constant, or proportional to each other after centring) get the minimum-norm solution of the centred and
+    scaled problem, which puts no weight on a constant column."""
+    x1 = np.asarray(x1, np.float64)
+    x2 = np.asarray(x2, np.float64)
+    y = np.asarray(y, np.float64)
+    m = np.array([x1.mean(), x2.mean()])
+    z = np.stack([x1, x2], 1) - m
+    sc = np.sqrt((z ** 2).sum(0))
+    sc[sc == 0.0] = 1.0
+    coef, *_ = np.linalg.lstsq(z / sc, y - y.mean(), rcond=1e-10)
+    c = coef / sc
+    return float(y.mean() - c @ m), float(c[0]), float(c[1])
+
+
+def pinball_loss2(x1, x2, y, q, c):
+    r = np.asarray(y, np.float64) - (c[0] + c[1] * np.asarray(x1, np.float64) + c[2] * np.asarray(x2, np.float64))
+    return float(np.where(r >= 0, q * r, (q - 1.0) * r).sum())
+
+
+def fit_quantile2(x1, x2, y, q):
+    """Quantile regression at level q with two regressors, as the same linear program as fit_quantile with one
+    more free variable.  Returns ((c0, c1, c2), loss); only the loss is unique."""
+    x1 = np.asarray(x1, np.float64)
+    x2 = np.asarray(x2, np.float64)
+    y = np.asarray(y, np.float64)
+    n = len(y)
+    # scaled columns keep the program well conditioned (x2 reaches 1e9)
+    s1 = max(np.abs(x1).max(), 1e-300)
+    s2 = max(np.abs(x2).max(), 1e-300)
+    c = np.concatenate([[0.0, 0.0, 0.0], np.full(n, q), np.full(n, 1.0 - q)])
+    a_eq = np.hstack([np.ones((n, 1)), (x1 / s1)[:, None], (x2 / s2)[:, None], np.eye(n), -np.eye(n)])
+    bounds = [(None, None)] * 3 + [(0, None)] * (2 * n)
+    res = linprog(c, A_eq=a_eq, b_eq=y, bounds=bounds, method="highs")
+    if res.status != 0:
+        raise RuntimeError(res.message)
+    coef = (float(res.x[0]), float(res.x[1] / s1), float(res.x[2] / s2))
+    return coef, pinball_loss2(x1, x2, y, q, coef)
+
+
 # ---- Request Classifier (Sec. 3.4) --------------------------------------------------------
 def classify_naive(modality: int) -> int:
     """text -> motorcycle, image -> car, video -> truck (modality codes 0, 1, 2)."""

@@ -156,6 +156,143 @@ int tcms_fit_quantile(const double* x, const double* y, int64_t n, double q, dou
   return TCMS_OK;
 }
 
+namespace {
+// centre and scale the two regressors (x2 reaches 1e9 for long videos); a constant column keeps scale 1
+struct Scaled2 {
+  std::vector<double> u, v;
+  double m1 = 0.0, m2 = 0.0, s1 = 1.0, s2 = 1.0;
+  Scaled2(const double* x1, const double* x2, int64_t n) : u((size_t)n), v((size_t)n) {
+    for (int64_t i = 0; i < n; ++i) { m1 += x1[i]; m2 += x2[i]; }
+    m1 /= (double)n;
+    m2 /= (double)n;
+    double q1 = 0.0, q2 = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+      q1 += (x1[i] - m1) * (x1[i] - m1);
+      q2 += (x2[i] - m2) * (x2[i] - m2);
+    }
+    if (q1 > 0.0) s1 = std::sqrt(q1);
+    if (q2 > 0.0) s2 = std::sqrt(q2);
+    for (int64_t i = 0; i < n; ++i) {
+      u[(size_t)i] = (x1[i] - m1) / s1;
+      v[(size_t)i] = (x2[i] - m2) / s2;
+    }
+  }
+  // coefficients of (1, u, v) -> coefficients of (1, x1, x2)
+  void unscale(double a0, double a1, double a2, double* coef) const {
+    coef[1] = a1 / s1;
+    coef[2] = a2 / s2;
+    coef[0] = a0 - coef[1] * m1 - coef[2] * m2;
+  }
+};
+}  // namespace
+
+int tcms_fit_linear2(const double* x1, const double* x2, const double* y, int64_t n, double* coef) {
+  if (!x1 || !x2 || !y || !coef || n < 1 || !finite_all(x1, n) || !finite_all(x2, n) || !finite_all(y, n))
+    return TCMS_E_INVALID_ARG;
+  const Scaled2 z(x1, x2, n);
+  double ym = 0.0;
+  for (int64_t i = 0; i < n; ++i) ym += y[i];
+  ym /= (double)n;
+  double suu = 0.0, svv = 0.0, suv = 0.0, suy = 0.0, svy = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    const double u = z.u[(size_t)i], v = z.v[(size_t)i], r = y[i] - ym;
+    suu += u * u; svv += v * v; suv += u * v; suy += u * r; svy += v * r;
+  }
+  // the columns have unit length (or are zero): det = 1 - cos^2 of the angle between them
+  const double det = suu * svv - suv * suv;
+  double a1, a2;
+  if (det > 1e-10) {
+    a1 = (svv * suy - suv * svy) / det;
+    a2 = (suu * svy - suv * suy) / det;
+  } else if (suu > 0.0 && svv > 0.0) {   // proportional columns: the minimum-norm solution shares the slope
+    a1 = 0.5 * suy;
+    a2 = suv > 0.0 ? a1 : -a1;
+  } else {                                // a constant column gets no weight
+    a1 = suu > 0.0 ? suy : 0.0;
+    a2 = svv > 0.0 ? svy : 0.0;
+  }
+  z.unscale(ym, a1, a2, coef);
+  return TCMS_OK;
+}
+
+double tcms_pinball_loss2(const double* x1, const double* x2, const double* y, int64_t n, double q,
+                          const double* coef) {
+  if (!x1 || !x2 || !y || !coef || n < 0) return std::numeric_limits<double>::quiet_NaN();
+  double s = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    const double r = y[i] - (coef[0] + coef[1] * x1[i] + coef[2] * x2[i]);
+    s += r >= 0.0 ? q * r : (q - 1.0) * r;
+  }
+  return s;
+}
+
+int tcms_fit_quantile2(const double* x1, const double* x2, const double* y, int64_t n, double q, double* coef,
+                       double* loss) {
+  if (!x1 || !x2 || !y || !coef || n < 1 || n > 4096 || !(q > 0.0 && q < 1.0) || !finite_all(x1, n) ||
+      !finite_all(x2, n) || !finite_all(y, n))
+    return TCMS_E_INVALID_ARG;
+  const Scaled2 z(x1, x2, n);
+  const std::vector<double>&u = z.u, &v = z.v;
+  auto loss_of = [&](double a0, double a1, double a2) {
+    double s = 0.0;
+    for (int64_t k = 0; k < n; ++k) {
+      const double r = y[k] - (a0 + a1 * u[(size_t)k] + a2 * v[(size_t)k]);
+      s += r >= 0.0 ? q * r : (q - 1.0) * r;
+    }
+    return s;
+  };
+  double best = std::numeric_limits<double>::infinity(), b0 = 0.0, b1 = 0.0, b2 = 0.0;
+  std::vector<std::pair<double, double>> bp;
+  bp.reserve((size_t)n);
+  // The optimum of the linear program is a plane through three data points.  For every pair of points with
+  // different regressors, the planes through both form a one-parameter family (slope vector = p0 + t * nrm);
+  // along t the loss is convex and piecewise linear with breakpoints where a third point falls on the plane,
+  // and its derivative rises by |b_k| there: the best member is a weighted quantile, as in the one-regressor fit.
+  for (int64_t i = 0; i < n; ++i) {
+    for (int64_t j = i + 1; j < n; ++j) {
+      const double du = u[(size_t)j] - u[(size_t)i], dv = v[(size_t)j] - v[(size_t)i];
+      const double dd = du * du + dv * dv;
+      if (dd == 0.0) continue;
+      const double dy = y[j] - y[i];
+      const double p0u = dy * du / dd, p0v = dy * dv / dd, nu = -dv, nv = du;
+      bp.clear();
+      double g = 0.0;
+      for (int64_t k = 0; k < n; ++k) {
+        const double eu = u[(size_t)k] - u[(size_t)i], ev = v[(size_t)k] - v[(size_t)i];
+        const double b = nu * eu + nv * ev;
+        if (b == 0.0) continue;
+        const double a = (y[k] - y[i]) - (p0u * eu + p0v * ev);
+        bp.emplace_back(a / b, std::fabs(b));
+        g -= b > 0.0 ? b * q : -b * (1.0 - q);
+      }
+      double t = 0.0;
+      if (!bp.empty()) {
+        std::sort(bp.begin(), bp.end());
+        t = bp.back().first;
+        for (const auto& e : bp) {
+          g += e.second;
+          if (g >= 0.0) { t = e.first; break; }
+        }
+      }
+      const double a1 = p0u + t * nu, a2 = p0v + t * nv;
+      const double a0 = y[i] - a1 * u[(size_t)i] - a2 * v[(size_t)i];
+      const double l = loss_of(a0, a1, a2);
+      if (l < best) { best = l; b0 = a0; b1 = a1; b2 = a2; }
+    }
+  }
+  if (!std::isfinite(best)) {   // every point has the same regressors: a q-quantile of y
+    std::vector<double> ys(y, y + n);
+    std::sort(ys.begin(), ys.end());
+    int64_t k = (int64_t)std::ceil(q * (double)n) - 1;
+    k = std::min<int64_t>(std::max<int64_t>(k, 0), n - 1);
+    b0 = ys[(size_t)k];
+    b1 = b2 = 0.0;
+  }
+  z.unscale(b0, b1, b2, coef);
+  if (loss) *loss = tcms_pinball_loss2(x1, x2, y, n, q, coef);
+  return TCMS_OK;
+}
+
 int tcms_classify_naive(int modality) {
   switch (modality) {
     case 0: return TCMS_MOTORCYCLE;

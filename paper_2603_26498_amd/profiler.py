@@ -56,9 +56,10 @@ def profile_requests(enc, items, reps=3, warmup=1):
     recs = []
     for it in items:
         if it.n_frames == 0:
-            recs.append({"modality": it.modality, "tokens": 0, "preprocess_ms": 0.0, "encode_ms": 0.0})
+            recs.append({"modality": it.modality, "tokens": 0, "seg_sq": 0, "preprocess_ms": 0.0, "encode_ms": 0.0})
             continue
         plan = enc.plan([it])
+        cu = plan.cu_seqlens
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         pre, encd = [], []
         for r in range(warmup + reps):
@@ -74,13 +75,22 @@ def profile_requests(enc, items, reps=3, warmup=1):
                 pre.append(ev[0].elapsed_time(ev[1]))
                 encd.append(ev[1].elapsed_time(ev[2]))
         recs.append({"modality": it.modality, "tokens": int(plan.info.n_tokens), "frames": it.n_frames,
+                     "seg_sq": int(sum((b - a) ** 2 for a, b in zip(cu[:-1], cu[1:]))),
                      "preprocess_ms": float(np.median(pre)), "encode_ms": float(np.median(encd))})
         plan.close()
     return recs
 
 
-def fit_impact_estimator(recs, q=0.9):
-    """Per modality: least-squares and q-quantile lines of (preprocess + encode) time against tokens."""
+def _seg_sq(r):
+    """Sum of the squared attention-segment lengths of a profiled request (one segment when not recorded)."""
+    return float(r.get("seg_sq", r["tokens"] ** 2))
+
+
+def fit_impact_estimator(recs, q=0.9, attention_term=False):
+    """Per modality: least-squares and q-quantile fits of (preprocess + encode) time against the tokens of the
+    request.  The paper's estimator keeps the models simple (Sec. 3.3): one regressor.  With attention_term the
+    sum of the squared attention-segment lengths joins as a second regressor - the encoder's attention work grows
+    with it, and for long videos it is most of the time."""
     models = {}
     for m in (IMAGE, VIDEO):
         sel = [r for r in recs if r["modality"] == m]
@@ -88,17 +98,28 @@ def fit_impact_estimator(recs, q=0.9):
             continue
         x = np.array([r["tokens"] for r in sel], float)
         y = np.array([r["preprocess_ms"] + r["encode_ms"] for r in sel], float)
-        ls, li = T.tcms_fit_linear(x, y)
-        qs, qi, ql = T.tcms_fit_quantile(x, y, q)
-        models[m] = {"linear": (ls, li), "quantile": (qs, qi), "q": q, "n": len(sel), "pinball": ql}
+        if attention_term:
+            x2 = np.array([_seg_sq(r) for r in sel], float)
+            lin = T.tcms_fit_linear2(x, x2, y)
+            qc, ql = T.tcms_fit_quantile2(x, x2, y, q)
+            models[m] = {"linear": (lin[1], lin[0], lin[2]), "quantile": (qc[1], qc[0], qc[2]), "q": q,
+                         "n": len(sel), "pinball": ql}
+        else:
+            ls, li = T.tcms_fit_linear(x, y)
+            qs, qi, ql = T.tcms_fit_quantile(x, y, q)
+            models[m] = {"linear": (ls, li), "quantile": (qs, qi), "q": q, "n": len(sel), "pinball": ql}
     return models
 
 
-def predict(models, modality, tokens, kind="quantile"):
+def predict(models, modality, tokens, kind="quantile", seg_sq=None):
+    """Estimated stage time in ms; models hold (slope, intercept[, coefficient of the squared-segment term])."""
     if modality == TEXT or modality not in models:
         return 0.0
-    s, i = models[modality][kind]
-    return max(0.0, i + s * tokens)
+    c = models[modality][kind]
+    t = c[1] + c[0] * tokens
+    if len(c) > 2:
+        t += c[2] * (tokens ** 2 if seg_sq is None else seg_sq)
+    return max(0.0, t)
 
 
 def estimator_report(models, recs):
@@ -110,10 +131,12 @@ def estimator_report(models, recs):
             continue
         y = np.array([r["preprocess_ms"] + r["encode_ms"] for r in sel])
         for kind in ("linear", "quantile"):
-            p = np.array([predict(models, m, r["tokens"], kind) for r in sel])
+            p = np.array([predict(models, m, r["tokens"], kind, _seg_sq(r)) for r in sel])
             err = p - y
-            lines.append(f"  {name:5s} {kind:8s}: slope {models[m][kind][0] * 1e3:8.4f} us/token, intercept "
-                         f"{models[m][kind][1]:8.3f} ms; n={len(sel)}; |err| mean {np.abs(err).mean():7.3f} ms, "
+            c = models[m][kind]
+            sq = f", {c[2] * 1e9:8.4f} ns/token^2" if len(c) > 2 else ""
+            lines.append(f"  {name:5s} {kind:8s}: slope {c[0] * 1e3:8.4f} us/token, intercept "
+                         f"{c[1]:8.3f} ms{sq}; n={len(sel)}; |err| mean {np.abs(err).mean():7.3f} ms, "
                          f"max {np.abs(err).max():7.3f} ms; under-estimated {100.0 * (err < 0).mean():5.1f} % of requests; "
                          f"request times {y.min():.2f}..{y.max():.2f} ms")
     return lines
@@ -212,6 +235,10 @@ def main():
                      f"{r['preprocess_ms']:8.3f} {r['encode_ms']:9.3f}")
     lines += ["", "fits on every second record, errors on the fitted records:"] + estimator_report(models, train)
     lines += ["errors on the held-out records:"] + estimator_report(models, test)
+    models2 = fit_impact_estimator(train, attention_term=True)
+    lines += ["", "the same with the sum of squared attention-segment lengths as a second regressor,",
+              "errors on the fitted records:"] + estimator_report(models2, train)
+    lines += ["errors on the held-out records:"] + estimator_report(models2, test)
     lines += ["", "policies on a Poisson trace (text : image : video = 200 : 24 : 2), service time = P90 estimate:"]
     full = fit_impact_estimator(recs)
     cm = fit_classifier(full, recs)

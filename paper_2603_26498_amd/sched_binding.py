@@ -34,6 +34,9 @@ SIGNATURES = {
     "tcms_fit_linear": (C.c_int, [_D, _D, C.c_int64, _D, _D]),
     "tcms_pinball_loss": (C.c_double, [_D, _D, C.c_int64, C.c_double, C.c_double, C.c_double]),
     "tcms_fit_quantile": (C.c_int, [_D, _D, C.c_int64, C.c_double, _D, _D, _D]),
+    "tcms_fit_linear2": (C.c_int, [_D, _D, _D, C.c_int64, _D]),
+    "tcms_pinball_loss2": (C.c_double, [_D, _D, _D, C.c_int64, C.c_double, _D]),
+    "tcms_fit_quantile2": (C.c_int, [_D, _D, _D, C.c_int64, C.c_double, _D, _D]),
     "tcms_classify_naive": (C.c_int, [C.c_int]),
     "tcms_cluster_fit": (C.c_int, [_D, C.c_int64, C.c_int, C.POINTER(tcms_cluster_model)]),
     "tcms_cluster_assign": (C.c_int, [C.POINTER(tcms_cluster_model), C.c_double, C.c_double]),
@@ -93,6 +96,32 @@ def tcms_fit_quantile(x, y, q):
     s, i, l = C.c_double(), C.c_double(), C.c_double()
     _check(lib().tcms_fit_quantile(px, py, len(x), q, C.byref(s), C.byref(i), C.byref(l)), "tcms_fit_quantile")
     return s.value, i.value, l.value
+
+
+def tcms_fit_linear2(x1, x2, y):
+    x1, p1 = _arr(x1)
+    x2, p2 = _arr(x2)
+    y, py = _arr(y)
+    coef = (C.c_double * 3)()
+    _check(lib().tcms_fit_linear2(p1, p2, py, len(y), coef), "tcms_fit_linear2")
+    return tuple(coef)
+
+
+def tcms_pinball_loss2(x1, x2, y, q, coef):
+    x1, p1 = _arr(x1)
+    x2, p2 = _arr(x2)
+    y, py = _arr(y)
+    return lib().tcms_pinball_loss2(p1, p2, py, len(y), q, (C.c_double * 3)(*coef))
+
+
+def tcms_fit_quantile2(x1, x2, y, q):
+    x1, p1 = _arr(x1)
+    x2, p2 = _arr(x2)
+    y, py = _arr(y)
+    coef = (C.c_double * 3)()
+    l = C.c_double()
+    _check(lib().tcms_fit_quantile2(p1, p2, py, len(y), q, coef, C.byref(l)), "tcms_fit_quantile2")
+    return tuple(coef), l.value
 
 
 def tcms_classify_naive(modality):

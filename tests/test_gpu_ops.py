@@ -229,6 +229,51 @@ def test_empty_inputs_are_no_ops():
     sync()
 
 
+def _bf16_round(v):
+    """fp64 -> nearest bf16 value (ties to even), as fp64; the fp32 step in between is harmless here because the
+    values tested are never within 2^-24 relative of a bf16 tie."""
+    u = np.asarray(v, np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("m,n,k", [(192, 64, 64), (16384 + 37, 2560, 128)])
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_gelu_epilogue_on_an_exact_grid(m, n, k, with_bias):
+    """The activation of the fc1 epilogue on known arguments.  Rows of A are one-hot, so the accumulator is exactly
+    one weight (plus an fp32 bias chosen so that the sum is exact): the weights run over every bf16 value with
+    2^-12 <= |x| <= 10, i.e. an exact grid that is dense near 0.  The bf16 output must be within one bf16 unit in
+    the last place of the rounded exact erf-form GELU (or 2^-22 where that is larger) for every argument; a tanh-form
+    or a sigmoid-form activation misses this by several units.  Both tile families are driven (small shape: 64-row
+    tiles; large shape: persistent 256-row tiles)."""
+    e, mant = np.meshgrid(np.arange(-12, 4), np.arange(128), indexing="ij")
+    mag = (np.ldexp(1.0 + mant / 128.0, e)).reshape(-1)
+    mag = mag[mag <= 10.0]
+    grid = np.concatenate([mag, -mag, [0.0]]).astype(np.float32)
+    assert np.array_equal(bf16_grid(grid), grid)
+    rng = np.random.default_rng(11)
+    w = grid[rng.integers(0, grid.size, (n, k))]
+    w.reshape(-1)[:grid.size] = grid                                  # every grid value occurs at least once
+    a = np.zeros((m, k), np.float32)
+    a[np.arange(m), np.arange(m) % k] = 1.0
+    # bias: multiples of 2^-13 below 2; |x| < 16 with a last place of 2^-19 fits the 24 bits of an fp32
+    bias = (rng.integers(-16000, 16000, n) * 2.0 ** -13).astype(np.float32) if with_bias else np.zeros(n, np.float32)
+    x = w.astype(np.float64).T[np.arange(m) % k] + bias.astype(np.float64)            # [m, n], exact
+    assert np.array_equal(x.astype(np.float32).astype(np.float64), x)
+    want = _bf16_round(oe.gelu(x))
+    c = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.tcmv_op_gemm(B.TCMV_BF16, B.EPI_GELU, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+    sync()
+    got = c.float().cpu().numpy().astype(np.float64)
+    ulp = np.ldexp(1.0, np.floor(np.log2(np.maximum(np.abs(want), 1e-300))).astype(np.int64) - 7)
+    tol = np.maximum(ulp, 2.0 ** -22)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (x[bad][:5], got[bad][:5], want[bad][:5])
+    # the pin has teeth: the tanh form of the activation, rounded the same way, breaks the bound
+    tanh_form = _bf16_round(0.5 * x * (1 + np.tanh(np.sqrt(2 / np.pi) * (x + 0.044715 * x ** 3))))
+    assert (np.abs(tanh_form - want) > tol).any()
+
+
 def test_gemm_bf16_large_tile_path_with_ragged_rows():
     """Enough 256x256 tiles to select the large-tile kernel, with a ragged last row tile."""
     rng = np.random.default_rng(77)

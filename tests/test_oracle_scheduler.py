@@ -75,6 +75,64 @@ def test_quantile_regression_residual_counts_and_constant_x():
     assert S.pinball_loss([0, 0], [1.0, -1.0], 0.9, 0.0, 0.0) == pytest.approx(0.9 + 0.1)
 
 
+def test_two_regressor_least_squares_against_normal_equations_and_exact_plane():
+    rng = np.random.default_rng(3)
+    t = rng.uniform(100, 33000, 60)
+    x2 = t ** 2                                         # what a one-segment request has: (sum of) squared length
+    y = 0.4 + 3e-3 * t + 2e-9 * x2 + rng.normal(0, 0.05, 60)
+    c = S.fit_linear2(t, x2, y)
+    a = np.stack([np.ones_like(t), t / 1e4, x2 / 1e8], 1)            # textbook normal equations, columns rescaled
+    ref = np.linalg.solve(a.T @ a, a.T @ y) / np.array([1.0, 1e4, 1e8])
+    assert np.allclose(c, ref, rtol=1e-7, atol=1e-12)
+    c = S.fit_linear2(t, x2, 7.0 - 0.5 * t + 1e-6 * x2)
+    assert np.allclose(c, (7.0, -0.5, 1e-6), rtol=1e-8)
+    # a regressor without information gets no weight: the fit is the one-regressor fit
+    s1, i1 = S.fit_linear(t, y)
+    assert np.allclose(S.fit_linear2(t, np.full(60, 5.0), y), (i1, s1, 0.0), rtol=1e-9, atol=1e-12)
+    # proportional regressors share the slope so that predictions equal the one-regressor fit
+    c = S.fit_linear2(t, 3.0 * t, y)
+    assert np.allclose(c[0] + c[1] * t + c[2] * 3.0 * t, i1 + s1 * t, rtol=1e-9)
+
+
+def _best_plane_through_three_points(x1, x2, y, q):
+    best = math.inf
+    for tri in itertools.combinations(range(len(y)), 3):
+        a = np.stack([np.ones(3), x1[list(tri)], x2[list(tri)]], 1)
+        if abs(np.linalg.det(a)) < 1e-9:
+            continue
+        best = min(best, S.pinball_loss2(x1, x2, y, q, np.linalg.solve(a, y[list(tri)])))
+    return best
+
+
+@pytest.mark.parametrize("q", [0.5, 0.9])
+def test_two_regressor_quantile_regression_against_vertex_enumeration(q):
+    """With three free coefficients a vertex of the linear program is a plane through three data points."""
+    rng = np.random.default_rng(4)
+    for n in (4, 9, 16):
+        x1 = rng.uniform(0, 10, n)
+        x2 = x1 ** 2 + rng.uniform(0, 5, n)
+        y = 1.0 + 0.3 * x1 + 0.05 * x2 + rng.gamma(2.0, 1.0, n)
+        c, loss = S.fit_quantile2(x1, x2, y, q)
+        assert abs(loss - _best_plane_through_three_points(x1, x2, y, q)) <= 1e-8 * max(1.0, loss)
+        assert abs(loss - S.pinball_loss2(x1, x2, y, q, c)) <= 1e-12 * max(1.0, loss)
+        # never worse than the best line in x1 alone, equal to it when the second regressor is constant
+        _, _, loss1 = S.fit_quantile(x1, y, q)
+        assert loss <= loss1 + 1e-9
+        assert S.fit_quantile2(x1, np.full(n, 2.0), y, q)[1] == pytest.approx(loss1, rel=1e-8, abs=1e-10)
+
+
+def test_two_regressor_quantile_regression_residual_counts_at_request_scale():
+    rng = np.random.default_rng(5)
+    t = rng.uniform(256, 33000, 120)
+    y = 0.5 + 4e-3 * t + 1.2e-7 * t ** 2 * (1 + 0.05 * rng.random(120))
+    c, _ = S.fit_quantile2(t, t ** 2, y, 0.9)
+    r = y - (c[0] + c[1] * t + c[2] * t ** 2)
+    assert (r < -1e-7).sum() <= 0.9 * 120 + 1e-9 <= (r <= 1e-7).sum() + 1e-9
+    assert np.abs(r).max() < 0.05 * y.max()             # the square term is followed, a line would miss by far more
+    s, i, _ = S.fit_quantile(t, y, 0.9)
+    assert np.abs(y - (i + s * t)).max() > 4 * np.abs(r).max()
+
+
 # ---- Request Classifier ----------------------------------------------------------------------
 def test_naive_classifier_follows_modality():
     assert [S.classify_naive(m) for m in (0, 1, 2)] == [S.MOTORCYCLE, S.CAR, S.TRUCK]

@@ -43,6 +43,23 @@ def test_estimator_fits_match_the_reference():
     assert len(P.estimator_report(models, recs)) == 4
 
 
+def test_estimator_with_the_attention_term_follows_the_videos():
+    recs = _records(np.random.default_rng(3))
+    one = P.fit_impact_estimator(recs)
+    two = P.fit_impact_estimator(recs, attention_term=True)
+    sel = [r for r in recs if r["modality"] == 2]
+    x = np.array([r["tokens"] for r in sel], float)
+    y = np.array([r["preprocess_ms"] + r["encode_ms"] for r in sel])
+    coef, loss = S.fit_quantile2(x, x ** 2, y, 0.9)
+    assert two[2]["pinball"] == pytest.approx(loss, rel=1e-8)
+    c = S.fit_linear2(x, x ** 2, y)
+    assert two[2]["linear"] == pytest.approx((c[1], c[0], c[2]), rel=1e-6)
+    e1 = np.abs([P.predict(one, 2, r["tokens"], "linear") for r in sel] - y).max()
+    e2 = np.abs([P.predict(two, 2, r["tokens"], "linear", r["tokens"] ** 2) for r in sel] - y).max()
+    assert e2 < 0.25 * e1                               # the records hold a square term; a line cannot follow it
+    assert len(P.estimator_report(two, recs)) == 4
+
+
 def test_classifier_trained_on_profile_separates_the_modalities_of_the_sweep():
     recs = _records(np.random.default_rng(1))
     models = P.fit_impact_estimator(recs)

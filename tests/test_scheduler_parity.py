@@ -46,6 +46,39 @@ def test_quantile_regression_reaches_the_minimum_of_the_linear_program(q, n):
     assert (r < -tol).sum() <= q * n + 1e-9 <= (r <= tol).sum() + 1e-9
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 17, 400])
+def test_two_regressor_least_squares(n):
+    rng = np.random.default_rng(n)
+    t = rng.uniform(64, 33000, n)
+    y = 1.5 + 0.004 * t + 1.1e-7 * t ** 2 + rng.normal(0, 2, n)
+    for x2 in (t ** 2, np.full(n, 9.0), 3.0 * t):          # informative, constant, proportional
+        c = T.tcms_fit_linear2(t, x2, y)
+        ref = S.fit_linear2(t, x2, y)
+        pred, pref = c[0] + c[1] * t + c[2] * x2, ref[0] + ref[1] * t + ref[2] * x2
+        assert np.allclose(pred, pref, rtol=1e-8, atol=1e-8)
+        if n >= 3:
+            assert np.allclose(c, ref, rtol=1e-6, atol=1e-9 * max(1.0, abs(ref[0])))
+
+
+@pytest.mark.parametrize("q", [0.9, 0.5])
+@pytest.mark.parametrize("n", [1, 2, 3, 10, 61, 150])
+def test_two_regressor_quantile_regression_reaches_the_minimum_of_the_linear_program(q, n):
+    rng = np.random.default_rng(100 * n + int(q * 10))
+    t = np.round(rng.uniform(64, 33000, n))
+    x2 = t ** 2 if n % 2 else t ** 2 * rng.uniform(0.3, 1.0, n)       # one segment, or several per request
+    y = 2.0 + 0.004 * t + 1.1e-7 * x2 + rng.gamma(2.0, 4.0, n)
+    c, loss = T.tcms_fit_quantile2(t, x2, y, q)
+    _, ref = S.fit_quantile2(t, x2, y, q)
+    assert loss == pytest.approx(ref, rel=1e-8, abs=1e-8)
+    assert S.pinball_loss2(t, x2, y, q, c) == pytest.approx(loss, rel=1e-12, abs=1e-12)
+    assert T.tcms_pinball_loss2(t, x2, y, q, c) == pytest.approx(loss, rel=1e-12, abs=1e-12)
+    # with a constant second regressor it is the one-regressor fit
+    c1, loss1 = T.tcms_fit_quantile2(t, np.full(n, 4.0), y, q)
+    assert loss1 == pytest.approx(T.tcms_fit_quantile(t, y, q)[2], rel=1e-9, abs=1e-9)
+    with pytest.raises(T.TcmsError):
+        T.tcms_fit_quantile2(t, x2, y, 1.0)
+
+
 def test_quantile_regression_degenerate_inputs():
     y = np.array([4.0, 1.0, 3.0, 2.0, 10.0])
     for q in (0.5, 0.9, 0.2):
