@@ -47,7 +47,11 @@ struct tcmv_plan {
   int n_windows = 0;
   int64_t max_win_len = 0;          // longest window (tokens)
   std::vector<float> lut;             // [3][256]
-  std::vector<PreStrip> strips;       // preprocessing work of the strip kernel (line segments copied or resampled into LDS)
+  std::vector<PreStrip> strips;       // preprocessing work of the strip kernel: copied strips, then (appended at the end of planning) the resampled ones
+  std::vector<PreStrip> strips_resampled;
+  int n_copy_strips = 0;
+  bool affine = false;                // bf16 normalisation table == bf16(fma(v, aff_scale, aff_off)) entry by entry
+  float aff_scale[3] = {0, 0, 0}, aff_off[3] = {0, 0, 0};
   std::vector<int32_t> run_rows;      // patch rows produced run by run (unaligned frames, other patch sizes, window order)
   int64_t n_patch_rows = 0, n_tokens = 0, t_vpad = 0;
   int n_segments = 0;
@@ -404,9 +408,25 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
       const bool strip_ok = d.window == 0 && preprocess_has_strip_kernel(d.patch, d.tpatch) && (di.resized || aligned);
       const int64_t n_rows = (int64_t)di.gt * di.gh * di.gw;
       if (strip_ok) {
+        const bool still = di.n_frames == 1;
+        std::vector<PreStrip>& list = di.resized ? p->strips_resampled : p->strips;
         for (int t = 0; t < di.gt; ++t)
           for (int ph = 0; ph < di.gh; ++ph)
-            for (int pw0 = 0; pw0 < di.gw; pw0 += kStripTokens) p->strips.push_back(PreStrip{item_idx, t, ph, pw0});
+            for (int pw0 = 0; pw0 < di.gw; pw0 += kStripTokens) {
+              PreStrip sp{};
+              sp.row_stride = di.src_w * 3;
+              sp.frame_stride = di.src_h * di.src_w * 3;               // source pixels per frame <= 2^28 (checked above)
+              sp.src = di.frames + (size_t)(still ? 0 : t * d.tpatch) * (size_t)sp.frame_stride +
+                       (size_t)(ph * d.patch) * (size_t)sp.row_stride + (size_t)pw0 * d.patch * 3;
+              // raster order, or merge-group-major order (strips start at even patch columns)
+              sp.row_base = d.merge == 2
+                  ? (int64_t)di.row0 + ((int64_t)(t * (di.gh >> 1) + (ph >> 1)) * (di.gw >> 1)) * 4 + (ph & 1) * 2 + (pw0 >> 1) * 4
+                  : (int64_t)di.row0 + (int64_t)(t * di.gh + ph) * di.gw + pw0;
+              sp.ntok = std::min(kStripTokens, di.gw - pw0);
+              sp.flags = (still ? kStripStill : 0) | (di.resized ? kStripResampled : 0);
+              sp.item = item_idx; sp.t = t; sp.ph = ph; sp.pw0 = pw0;
+              list.push_back(sp);
+            }
       } else {
         for (int64_t r = 0; r < n_rows; ++r) p->run_rows.push_back((int32_t)(di.row0 + r));
       }
@@ -504,6 +524,19 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
       if (d.dtype == TCMV_BF16) x = round_bf16_host(x);
       p->lut[c * 256 + v] = x;
     }
+  // The bf16 strip kernel may compute the normalised value (one fused multiply-add, then the conversion to bf16,
+  // both correctly rounded on host and device alike) instead of looking it up - but only if that reproduces the
+  // table, which holds the contract's arithmetic, in all 768 entries.
+  p->affine = d.dtype == TCMV_BF16;
+  for (int c = 0; c < 3 && p->affine; ++c) {
+    p->aff_scale[c] = (float)(1.0 / (255.0 * (double)d.std[c]));
+    p->aff_off[c] = (float)(-(double)d.mean[c] / (double)d.std[c]);
+    for (int v = 0; v < 256; ++v)
+      if (round_bf16_host(std::fmaf((float)v, p->aff_scale[c], p->aff_off[c])) != p->lut[c * 256 + v]) p->affine = false;
+  }
+  p->n_copy_strips = (int)p->strips.size();
+  p->strips.insert(p->strips.end(), p->strips_resampled.begin(), p->strips_resampled.end());
+  p->strips_resampled.clear();
   size_t off = 0;
   p->off_items = place(off, p->items);
   p->off_prow_item = place(off, p->prow_item);
@@ -626,6 +659,9 @@ int tcmv_preprocess(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_meta, void*
   a.out_bf16 = ctx->desc.dtype == TCMV_BF16;
   a.merge = ctx->desc.merge;
   a.strips = dev<PreStrip>(d_meta, p->off_strips); a.n_strips = (int)p->strips.size();
+  a.n_copy_strips = p->n_copy_strips;
+  a.affine = p->affine;
+  for (int c = 0; c < 3; ++c) { a.aff_scale[c] = p->aff_scale[c]; a.aff_off[c] = p->aff_off[c]; }
   a.run_rows = dev<int32_t>(d_meta, p->off_run_rows); a.n_run_rows = (int64_t)p->run_rows.size();
   hipError_t e = timed(ctx, TCMV_K_PREPROCESS, (hipStream_t)stream, [&] { return launch_preprocess(a, (hipStream_t)stream); });
   if (e != hipSuccess) return fail_hip(ctx, e, "preprocess launch");

@@ -7,8 +7,9 @@
 //    16 horizontally adjacent patches of one patch line, copies their tpatch*patch
 //    source line segments into LDS with coalesced 4-byte loads (every source byte is
 //    read from HBM exactly once, all loads of a thread in flight together), then
-//    produces the patch rows from LDS through a 3x256 table of already-rounded
-//    normalised values; on the bf16 path a wave takes whole rows and its lanes write
+//    produces the patch rows from LDS, normalising through a 3x256 table of already-rounded
+//    values or, for bf16 output where the host has verified that it gives the same 768 values,
+//    by one fused multiply-add and the hardware's bf16 conversion; on the bf16 path a wave takes whole rows and its lanes write
 //    consecutive dwords (element pairs) of a row, on the fp32 path a thread writes runs;
 //    resampled requests go the same way, except that the LDS lines are not copied but
 //    computed: the strip's destination pixels, blended from their four source taps;
@@ -110,24 +111,28 @@ __global__ __launch_bounds__(256) void preprocess_kernel(PreprocArgs a, int runs
 }
 
 // Strip kernel: see the file comment.  Only instantiated for compile-time patch sizes.
-template <int P_, int TP_, bool BF16>
-__global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, int runs_per_row, int data_runs) {
+// RES: the strips of this launch are resampled ones (they need tap tables in LDS; the copy instantiation does
+//      without them, which lets one more workgroup live on a compute unit).
+// AFF: the normalised bf16 value is computed - one fused multiply-add and the hardware's round-to-nearest-even
+//      conversion, which the host has checked against all 768 table entries - instead of looked up: no table
+//      in LDS, no bank conflicts between lanes that hold different pixel values.
+template <int P_, int TP_, bool BF16, bool AFF, bool RES>
+__global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, int first, int runs_per_row, int data_runs) {
   constexpr int P = P_ ? P_ : 1, TP = TP_ ? TP_ : 1;
   constexpr int SEG = kStripTokens * P * 3;              // bytes of one line segment (multiple of 4)
   static_assert(SEG % 4 == 0, "segment size");
-  __shared__ float lut[768];
+  __shared__ float lut[AFF ? 1 : 768];
   // lanes that work on neighbouring lines read the same byte offset of each: the line stride is an odd number
   // of dwords so that those reads fall into different banks
   __shared__ __attribute__((aligned(16))) uint8_t seg[TP * P][SEG + 4];
-  const PreStrip sp = a.strips[blockIdx.x];
-  const ItemDev it = a.items[sp.item];
-  const int ntok = min(kStripTokens, it.gw - sp.pw0);
+  const PreStrip sp = a.strips[first + blockIdx.x];
+  const int ntok = sp.ntok;
   const int nbytes = ntok * P * 3;
-  const bool still = it.n_frames == 1;                   // a still image is its own second frame
+  const bool still = sp.flags & kStripStill;                       // a still image is its own second frame
   const int nlines = still ? P : TP * P;
-  const int row_stride = it.src_w * 3;
-  for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
-  if (!it.resized) {
+  if constexpr (!AFF)
+    for (int i = threadIdx.x; i < 768; i += 256) lut[i] = a.lut[i];
+  if constexpr (!RES) {
     // source line segments -> LDS, 4 bytes per lane, then the (at most 3) tail bytes of each line.  All loads
     // of a thread are issued before the first is used (a fixed-count loop over the full strip width, lanes
     // beyond the strip's own width masked off), so a workgroup has its whole input in flight at once.
@@ -142,8 +147,7 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
         const int line = i / NDW, dw = i - line * NDW;
         v[j] = 0u;
         if (line < nlines && dw < ndw) {
-          const int f = still ? 0 : sp.t * TP + line / P;
-          const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
+          const uint8_t* src = sp.src + (size_t)(line / P) * sp.frame_stride + (size_t)(line % P) * sp.row_stride;
           v[j] = reinterpret_cast<const uint32_t*>(src)[dw];
         }
       }
@@ -157,11 +161,9 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
     const int ntail = nbytes & 3;
     for (int i = threadIdx.x; i < nlines * ntail; i += 256) {
       const int line = i / ntail, b = (ndw << 2) + (i - line * ntail);
-      const int f = still ? 0 : sp.t * TP + line / P;
-      const uint8_t* src = it.frames + ((size_t)f * it.src_h + (size_t)(sp.ph * P + line % P)) * row_stride + (size_t)sp.pw0 * P * 3;
-      seg[line][b] = src[b];
+      seg[line][b] = sp.src[(size_t)(line / P) * sp.frame_stride + (size_t)(line % P) * sp.row_stride + b];
     }
-  } else {
+  } else if constexpr (RES) {
     // Resampled request: the strip's destination pixels are computed into the same LDS lines (as the uint8
     // values a resized frame would hold), so everything after this point is shared with the copy case.
     // Taps and weights of the strip's columns and lines are worked out once per workgroup; a thread then
@@ -169,6 +171,8 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
     // source pixels) and blends the three channels of each with the same four weights.
     __shared__ int col_c0[kStripTokens * P], col_c1[kStripTokens * P], col_fx[kStripTokens * P];
     __shared__ int line_r0[TP * P], line_r1[TP * P], line_fy[TP * P];
+    const ItemDev it = a.items[sp.item];
+    const int row_stride = it.src_w * 3;
     const int npx = ntok * P;
     for (int x = threadIdx.x; x < npx; x += 256) {
       int c0, c1, fx;
@@ -200,13 +204,8 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
   }
   __syncthreads();
   // patch row of token (t, ph, pw): raster order, or merge-group-major order
-  const int64_t row_line = (a.merge == 2)
-      ? (int64_t)it.row0 + ((int64_t)(sp.t * (it.gh >> 1) + (sp.ph >> 1)) * (it.gw >> 1)) * 4 + (sp.ph & 1) * 2
-      : (int64_t)it.row0 + (int64_t)(sp.t * it.gh + sp.ph) * it.gw;
-  auto row_of = [&](int tok) -> int64_t {
-    const int pw = sp.pw0 + tok;
-    return (a.merge == 2) ? row_line + (pw >> 1) * 4 + (pw & 1) : row_line + pw;
-  };
+  const int64_t row_base = sp.row_base;
+  auto row_of = [&](int tok) -> int64_t { return (a.merge == 2) ? row_base + (tok >> 1) * 4 + (tok & 1) : row_base + tok; };
   typedef typename std::conditional<BF16, uint16_t, float>::type out_t;
   if constexpr (BF16 && P % 2 == 0) {
     // bf16: a lane produces pairs of neighbouring elements (dwords of a patch row) and consecutive lanes
@@ -220,6 +219,7 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
     constexpr int NJ = (PAIRS + 63) / 64;                // dwords per lane and row
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int soff[NJ], lbase[NJ];                             // byte offset of the pair's first pixel in seg (token 0), table row
+    float sc[NJ], of[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int e = lane + 64 * j;
@@ -229,6 +229,7 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
         const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
         soff[j] = ((still ? 0 : tt) * P + py) * (SEG + 4) + c + 6 * i;
         lbase[j] = c * 256;
+        if constexpr (AFF) { sc[j] = a.aff_scale[c]; of[j] = a.aff_off[c]; }
       }
     }
     const uint8_t* seg0 = &seg[0][0];
@@ -242,7 +243,8 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
           uint32_t val = 0u;
           if (soff[j] >= 0) {
             const uint8_t* px = sb + soff[j];
-            val = (__float_as_uint(lut[lbase[j] + px[0]]) >> 16) | (__float_as_uint(lut[lbase[j] + px[3]]) & 0xFFFF0000u);
+            if constexpr (AFF) val = pack_bf16x2(__builtin_fmaf((float)px[0], sc[j], of[j]), __builtin_fmaf((float)px[3], sc[j], of[j]));
+            else val = (__float_as_uint(lut[lbase[j] + px[0]]) >> 16) | (__float_as_uint(lut[lbase[j] + px[3]]) & 0xFFFF0000u);
           }
           orow[e] = val;
         }
@@ -283,9 +285,19 @@ static void launch_pp(const PreprocArgs& a, hipStream_t s) {
     else hipLaunchKernelGGL((preprocess_kernel<P_, TP_, false>), grid, block, 0, s, a, runs_per_row, data_runs);
   }
   if (a.n_strips > 0 && P_ != 0) {
-    dim3 grid((unsigned)a.n_strips), block(256);
-    if (a.out_bf16) hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, true>), grid, block, 0, s, a, runs_per_row, data_runs);
-    else hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, false>), grid, block, 0, s, a, runs_per_row, data_runs);
+    auto go = [&](auto res, int first, int count) {
+      constexpr bool RES = decltype(res)::value;
+      if (count <= 0) return;
+      dim3 grid((unsigned)count), block(256);
+      if (a.out_bf16 && a.affine && P_ % 2 == 0)
+        hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, true, true, RES>), grid, block, 0, s, a, first, runs_per_row, data_runs);
+      else if (a.out_bf16)
+        hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, true, false, RES>), grid, block, 0, s, a, first, runs_per_row, data_runs);
+      else
+        hipLaunchKernelGGL((preprocess_strip_kernel<P_, TP_, false, false, RES>), grid, block, 0, s, a, first, runs_per_row, data_runs);
+    };
+    go(std::false_type{}, 0, a.n_copy_strips);
+    go(std::true_type{}, a.n_copy_strips, a.n_strips - a.n_copy_strips);
   }
 }
 
@@ -297,6 +309,7 @@ bool preprocess_has_strip_kernel(int patch, int tpatch) {
 hipError_t launch_preprocess(const PreprocArgs& a, hipStream_t s) {
   if (a.rows == 0) return hipSuccess;
   if (a.n_strips > 0 && !preprocess_has_strip_kernel(a.patch, a.tpatch)) return hipErrorInvalidValue;
+  if (a.n_copy_strips < 0 || a.n_copy_strips > a.n_strips) return hipErrorInvalidValue;
   // the bf16 strip kernel writes dwords of rows of (K rounded up to 64) elements
   if (a.n_strips > 0 && a.out_bf16 && (a.k_pad != (a.k + 63) / 64 * 64 || reinterpret_cast<uintptr_t>(a.patches) % 16))
     return hipErrorInvalidValue;

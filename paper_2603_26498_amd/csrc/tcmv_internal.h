@@ -17,8 +17,20 @@ struct ItemDev {
 };
 
 // One unit of preprocessing work of the strip kernel: up to kStripTokens horizontally
-// adjacent patches of one patch line of one frame group.
-struct PreStrip { int item, t, ph, pw0; };
+// adjacent patches of one patch line of one frame group.  A copied strip (source size ==
+// target size) is described completely here, so that a workgroup needs one scalar load
+// and no dependent second one before it can request its pixels; a resampled strip also
+// reads its request's ItemDev.
+struct PreStrip {
+  const uint8_t* src;       // copied strips: first byte of the strip in its first source line (first frame of the group)
+  int64_t row_base;         // patch row of the strip's first token
+  int32_t row_stride;       // bytes between source lines
+  int32_t frame_stride;     // bytes between frames
+  int32_t ntok;             // tokens of the strip (1..kStripTokens)
+  int32_t flags;            // bit 0: still image (its one frame fills the temporal patch), bit 1: resampled
+  int32_t item, t, ph, pw0; // request, frame group, patch line, first patch column
+};
+constexpr int kStripStill = 1, kStripResampled = 2;
 constexpr int kStripTokens = 16;
 
 // One unit of attention work: a tile of query rows of one segment.
@@ -93,7 +105,11 @@ struct PreprocArgs {
   int patch, tpatch, k, k_pad;
   int out_bf16;
   int merge;
-  const PreStrip* strips; int n_strips;         // requests copied line by line through LDS
+  const PreStrip* strips; int n_strips;         // strips staged through LDS: n_copy_strips copied ones first, then the resampled ones
+  int n_copy_strips;
+  // bf16 output: every table entry equals bf16(fma(v, aff_scale[c], aff_off[c])) (checked by the host for all 768),
+  // so the kernel may compute instead of looking up
+  int affine; float aff_scale[3], aff_off[3];
   const int32_t* run_rows; int64_t n_run_rows;  // patch rows produced run by run (resampled or unaligned requests)
 };
 

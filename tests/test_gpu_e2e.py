@@ -88,6 +88,41 @@ def test_preprocess_layouts_and_general_normalisation(dtype, patch, tpatch, merg
     check_patches(wl, oracle.run(wl, stages=("preprocess",)), patches)
 
 
+def _fma_form_reproduces_table(mean, std):
+    """Whether bf16(fma(v, 1/(255 std), -mean/std)) in fp32 equals the contract's bf16(fp32((v/255 - mean)/std)) for
+    every pixel value (the product v * scale fits a double exactly, so rounding the double sum once to fp32 is the
+    fused multiply-add)."""
+    v = np.arange(256, dtype=np.float64)
+    table = workloads.snap_to_bf16_grid(((v / 255.0 - mean) / std).astype(np.float32))
+    sc, of = np.float32(1.0 / (255.0 * std)), np.float32(-mean / std)
+    return np.array_equal(table, workloads.snap_to_bf16_grid((v * np.float64(sc) + np.float64(of)).astype(np.float32)))
+
+
+@pytest.mark.parametrize("first_channel,computed", [((0.5, 0.5), True), ((0.3121532201766968, 0.4928024709224701), False)])
+def test_bf16_normalisation_computed_or_looked_up_is_the_table(first_channel, computed):
+    """The bf16 strip kernel computes the normalised value with one fused multiply-add where that gives the table's
+    768 values, and looks it up where it does not (here: one entry of the first channel differs).  Either way the
+    patches are the reference's, bit for bit; copied and resampled strips, a video and still images."""
+    mean = (first_channel[0], float(np.float32(0.456)), float(np.float32(0.406)))
+    std = (first_channel[1], float(np.float32(0.224)), float(np.float32(0.225)))
+    assert all(_fma_form_reproduces_table(m, s) for m, s in zip(mean, std)) == computed
+    desc = workloads.ModelDesc(dtype="bf16", layers=0, d=128, heads=2, mlp=128, patch=14, tpatch=2, merge=2,
+                               mean=mean, std=std)
+    rng = np.random.default_rng(6)
+    items = [workloads.Item(1, 1, 84, 532, 84, 532, workloads.random_frames(rng, 1, 84, 532)),       # 38 tokens wide: strips of 16, 16, 6
+             workloads.Item(2, 4, 56, 476, 56, 476, workloads.random_frames(rng, 4, 56, 476)),       # 34 wide: 16, 16, 2
+             workloads.Item(1, 1, 61, 333, 56, 308, workloads.random_frames(rng, 1, 61, 333)),       # resampled
+             workloads.Item(2, 2, 100, 90, 84, 112, workloads.random_frames(rng, 2, 100, 90))]
+    # every pixel value occurs in every channel of the first image
+    items[0].frames.reshape(-1, 3)[:256] = np.arange(256, dtype=np.uint8)[:, None]
+    wl = workloads.Workload("normalisation", desc, items, workloads.make_weights(desc, 1))
+    enc = VisionEncoder(desc, wl.weights)
+    pl = enc.plan(items)
+    patches = enc.preprocess(pl)
+    torch.cuda.synchronize()
+    check_patches(wl, oracle.run(wl, stages=("preprocess",)), patches)
+
+
 def test_text_only_and_empty_batches_launch_nothing():
     wl = workloads.small_config(5)
     enc = VisionEncoder(wl.desc, wl.weights)
