@@ -281,6 +281,25 @@ def run_workload(config, steps, warmup, layers=None, table_steps=None):
     # ---- untimed pass for the per-class table
     n_tab = table_steps if table_steps is not None else min(steps, 5)
     prof = profiled(n_tab, -1) if n_tab > 0 else {}
+    # ---- what a kernel that only moves the preprocess stage's bytes reaches, at the same point of a step (its
+    # buffers were last touched a whole step ago, like the frames and the patch buffer)
+    stream_us = None
+    if n_tab > 0 and Tp > 0:
+        in_bytes = sum(it.frames.size for it in wl.items if it.n_frames > 0) // 16 * 16
+        out_bytes = patches.numel() * patches.element_size() // 16 * 16
+        s_in = torch.zeros(in_bytes, dtype=torch.uint8, device="cuda:0")
+        s_out = torch.empty(out_bytes, dtype=torch.uint8, device="cuda:0")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(n_tab + 1):
+            step()
+            e0.record(stream)
+            B.tcmv_op_stream(s_in, in_bytes, s_out, out_bytes, sp)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3)
+        stream_us = float(np.median(ts[1:]))
+        del s_in, s_out
 
     ms_per_step = elapsed / steps * 1e3
     fl = algorithmic_flops(desc, cu, Tp, wl.items)
@@ -299,6 +318,11 @@ def run_workload(config, steps, warmup, layers=None, table_steps=None):
         if name in by:
             e["gbs"] = round(by[name] / (per_step_ms * 1e-3) / 1e9, 1)
             e["frac_of_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        if name == "preprocess" and stream_us:
+            # a plain read-once / write-once kernel over the stage's own byte counts (frames in, padded patch rows
+            # out), timed the same way at the same point of the step
+            e["stream_same_bytes_us"] = round(stream_us, 2)
+            e["frac_of_stream_same_bytes"] = round(stream_us / e["avg_launch_us"], 4)
         if name == "layernorm":
             # the same launches against the byte count with bf16 on both sides (4 d bytes per row): the kernel
             # reads the fp32 residual stream, so it moves 6 d

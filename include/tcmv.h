@@ -276,6 +276,13 @@ int tcmv_profile_read(tcmv_ctx *ctx, double *ms, int64_t *launches);
 int tcmv_op_layernorm(int dtype, const float *d_x, const float *d_gamma, const float *d_beta,
                       void *d_y, int64_t rows, int d, float eps, void *stream);
 
+/* Bandwidth reference, no part of the path: reads in_bytes from d_in once and
+ * writes out_bytes to d_out once (the words written are the XOR of words read, so the
+ * reads cannot be dropped).  Timed beside a bandwidth-bound kernel with the same byte
+ * counts it shows what that kernel could reach at best at its size.  Sizes and
+ * pointers must be multiples of 16 (else TCMV_E_INVALID_ARG); either size may be 0. */
+int tcmv_op_stream(const void *d_in, size_t in_bytes, void *d_out, size_t out_bytes, void *stream);
+
 /* C = epilogue(A * W^T + bias).  A [m, k], W [n, k], both bf16 (k % 64 == 0,
  * n % 8 == 0) or fp32.  epilogue: 0: store (bf16 / fp32 by dtype);
  * 1: GELU (erf form; the bf16 path evaluates it to within 3.5e-5 absolute, and

@@ -81,6 +81,7 @@ SIGNATURES = {
     "tcmv_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "tcmv_op_layernorm": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                     C.c_float, C.c_void_p]),
+    "tcmv_op_stream": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tcmv_op_gemm": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                C.c_int, C.c_void_p]),
     "tcmv_op_attention_workspace": (C.c_size_t, [C.c_int, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int]),
@@ -267,6 +268,12 @@ def tcmv_op_layernorm(dtype, d_x, d_gamma, d_beta, d_y, rows, d, eps, stream=Non
     rc = lib().tcmv_op_layernorm(dtype, _ptr(d_x), _ptr(d_gamma), _ptr(d_beta), _ptr(d_y), rows, d, eps, stream)
     if rc != TCMV_OK:
         raise TcmvError(rc, "tcmv_op_layernorm")
+
+
+def tcmv_op_stream(d_in, in_bytes, d_out, out_bytes, stream=None):
+    rc = lib().tcmv_op_stream(_ptr(d_in), in_bytes, _ptr(d_out), out_bytes, stream)
+    if rc != TCMV_OK:
+        raise TcmvError(rc, "tcmv_op_stream")
 
 
 def tcmv_op_gemm(dtype, epilogue, d_a, d_w, d_bias, d_c, m, n, k, stream=None):

@@ -869,6 +869,13 @@ int tcmv_op_layernorm(int dtype, const float* d_x, const float* d_gamma, const f
              ? TCMV_OK : TCMV_E_HIP;
 }
 
+int tcmv_op_stream(const void* d_in, size_t in_bytes, void* d_out, size_t out_bytes, void* stream) {
+  if ((in_bytes && !d_in) || (out_bytes && !d_out)) return TCMV_E_INVALID_ARG;
+  if (in_bytes % 16 || out_bytes % 16 || reinterpret_cast<uintptr_t>(d_in) % 16 || reinterpret_cast<uintptr_t>(d_out) % 16)
+    return TCMV_E_INVALID_ARG;
+  return launch_stream_ref(d_in, in_bytes, d_out, out_bytes, (hipStream_t)stream) == hipSuccess ? TCMV_OK : TCMV_E_HIP;
+}
+
 int tcmv_op_gemm(int dtype, int epilogue, const void* d_a, const void* d_w, const float* d_bias, void* d_c,
                  int64_t m, int n, int k, void* stream) {
   const bool gated = epilogue == EPI_GATED;

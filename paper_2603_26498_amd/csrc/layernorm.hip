@@ -79,6 +79,28 @@ static hipError_t launch_ln_t(const float* x, const float* g, const float* b, vo
   return hipGetLastError();
 }
 
+// Reference for the bandwidth-bound kernels: n_in 16-byte words read once, n_out 16-byte words written once, no
+// other work - what a kernel that moves these bytes can reach at best at this size.
+__global__ __launch_bounds__(256) void stream_ref_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                         size_t n_in, size_t n_out) {
+  const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x, nt = (size_t)gridDim.x * 256;
+  uint4 acc = {0u, 0u, 0u, 0u};
+  for (size_t i = tid; i < n_in; i += nt) {
+    const uint4 v = in[i];
+    acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+  }
+  for (size_t i = tid; i < n_out; i += nt) out[i] = acc;
+}
+
+hipError_t launch_stream_ref(const void* in, size_t in_bytes, void* out, size_t out_bytes, hipStream_t s) {
+  if (in_bytes % 16 || out_bytes % 16 || reinterpret_cast<uintptr_t>(in) % 16 || reinterpret_cast<uintptr_t>(out) % 16)
+    return hipErrorInvalidValue;
+  if (in_bytes + out_bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(stream_ref_kernel, dim3(2048), dim3(256), 0, s, reinterpret_cast<const uint4*>(in),
+                     reinterpret_cast<uint4*>(out), in_bytes / 16, out_bytes / 16);
+  return hipGetLastError();
+}
+
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d, float eps,
                             int out_bf16, hipStream_t s, int rms) {
   if (rows == 0) return hipSuccess;

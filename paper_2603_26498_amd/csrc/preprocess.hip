@@ -229,24 +229,45 @@ __global__ __launch_bounds__(256) void preprocess_strip_kernel(PreprocArgs a, in
         const int py = run % P, tt = (run / P) % TP, c = run / (P * TP);
         soff[j] = ((still ? 0 : tt) * P + py) * (SEG + 4) + c + 6 * i;
         lbase[j] = c * 256;
-        if constexpr (AFF) { sc[j] = a.aff_scale[c]; of[j] = a.aff_off[c]; }
+      }
+      if constexpr (AFF) {
+        // padding dwords read byte 0 of the strip and multiply it by zero: the loop below has no branches, so the
+        // LDS reads of all dwords of a row are in flight together
+        const int c = lbase[j] >> 8;
+        sc[j] = soff[j] >= 0 ? a.aff_scale[c] : 0.f;
+        of[j] = soff[j] >= 0 ? a.aff_off[c] : 0.f;
+        soff[j] = max(soff[j], 0);
       }
     }
     const uint8_t* seg0 = &seg[0][0];
     for (int tok = wave; tok < ntok; tok += 4) {
       const uint8_t* sb = seg0 + tok * P * 3;
       uint32_t* orow = reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.patches) + (size_t)row_of(tok) * KP);
+      if constexpr (AFF) {
+        uint32_t b0[NJ], b1[NJ];
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const int e = lane + 64 * j;
-        if (e < PAIRS) {
-          uint32_t val = 0u;
-          if (soff[j] >= 0) {
-            const uint8_t* px = sb + soff[j];
-            if constexpr (AFF) val = pack_bf16x2(__builtin_fmaf((float)px[0], sc[j], of[j]), __builtin_fmaf((float)px[3], sc[j], of[j]));
-            else val = (__float_as_uint(lut[lbase[j] + px[0]]) >> 16) | (__float_as_uint(lut[lbase[j] + px[3]]) & 0xFFFF0000u);
+        for (int j = 0; j < NJ; ++j) {
+          const uint8_t* px = sb + soff[j];
+          b0[j] = px[0]; b1[j] = px[3];
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int e = lane + 64 * j;
+          const uint32_t val = pack_bf16x2(__builtin_fmaf((float)b0[j], sc[j], of[j]), __builtin_fmaf((float)b1[j], sc[j], of[j]));
+          if (64 * j + 63 < PAIRS || e < PAIRS) orow[e] = val;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int e = lane + 64 * j;
+          if (e < PAIRS) {
+            uint32_t val = 0u;
+            if (soff[j] >= 0) {
+              const uint8_t* px = sb + soff[j];
+              val = (__float_as_uint(lut[lbase[j] + px[0]]) >> 16) | (__float_as_uint(lut[lbase[j] + px[3]]) & 0xFFFF0000u);
+            }
+            orow[e] = val;
           }
-          orow[e] = val;
         }
       }
     }

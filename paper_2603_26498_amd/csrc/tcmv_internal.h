@@ -118,6 +118,7 @@ bool preprocess_has_strip_kernel(int patch, int tpatch);
 // rms != 0: RMSNorm (no mean subtraction, b is not read)
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* y, int64_t rows, int d,
                             float eps, int out_bf16, hipStream_t s, int rms = 0);
+hipError_t launch_stream_ref(const void* in, size_t in_bytes, void* out, size_t out_bytes, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // true when launch_gemm_bf16 computes the key-norm maxima in the epilogue of an m x n x k QKV projection whose key
 // columns are [qcols, 2 qcols) with heads of dh columns (the wave tiles must line up with the heads)

@@ -376,3 +376,30 @@ def test_attention_mixed_norm_bounds_in_one_launch():
     small[:, :dh] = qkv[:, :dh] / 7.0
     got2 = _attn("bf16", bf16_grid(small), [int(c) for c in cu], d, heads)
     assert np.array_equal(got[:, dh:], got2[:, dh:])
+
+
+# ---------------------------------------------------------------- bandwidth reference
+def test_stream_reference_reads_and_writes_what_it_says():
+    """Words written are the XOR of the words each thread read (threads stride over the input), so no read can be
+    dropped; a size of zero on either side is allowed, misaligned sizes are refused."""
+    nt = 2048 * 256
+    n_in, n_out = nt + nt // 2 + 5, nt + 77
+    rng = np.random.default_rng(0)
+    src = rng.integers(0, 2 ** 32, (n_in, 4), dtype=np.uint64).astype(np.uint32)
+    acc = np.zeros((nt, 4), np.uint32)
+    for k in range(0, n_in, nt):
+        blk = src[k:k + nt]
+        acc[:len(blk)] ^= blk
+    want = acc[np.arange(n_out) % nt]
+    d_in = torch.from_numpy(src.view(np.int32)).to(DEV)
+    d_out = torch.zeros((n_out, 4), dtype=torch.int32, device=DEV)
+    B.tcmv_op_stream(d_in, n_in * 16, d_out, n_out * 16)
+    sync()
+    assert np.array_equal(d_out.cpu().numpy().view(np.uint32), want)
+    B.tcmv_op_stream(None, 0, d_out, 16 * 10)             # nothing read: zeros written
+    B.tcmv_op_stream(d_in, 16 * 10, None, 0)
+    B.tcmv_op_stream(None, 0, None, 0)
+    sync()
+    assert not d_out[:10].any() and np.array_equal(d_out[10:].cpu().numpy().view(np.uint32), want[10:])
+    with pytest.raises(B.TcmvError):
+        B.tcmv_op_stream(d_in, 24, d_out, 16)
