@@ -30,11 +30,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_attention_hbm_traffic.txt).
+# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_hbm_traffic.txt; both copies of the kernel).
 # Valid only for the kernel code it was taken with: reported as null once that file changes (comments aside).
-ATTN_TRAFFIC = {"source_sha256": "b6484aa7c8ac28857c81e4c7acf0a50221946f1560924ffb7ebd29f6d2ab6e02",
+ATTN_TRAFFIC = {"source_sha256": "68dce7835300ddf2ac92702b49ae9438fe601a5837f8e6f8db99eb43d43b6e8c",
                 "workload": "cfg4_video64x448_vit32x1280_proj3584",
-                "fetch_bytes": 639557 * 1024, "write_bytes": 82436 * 1024}
+                "fetch_bytes": 557308 * 1024, "write_bytes": 82672 * 1024}
 
 
 def source_fingerprint(path):
@@ -344,7 +344,7 @@ def run_workload(config, steps, warmup, layers=None, table_steps=None):
     if roof["traffic"] is not None:
         roof["traffic_detail"] = {"fetch_bytes": ATTN_TRAFFIC["fetch_bytes"], "write_bytes": ATTN_TRAFFIC["write_bytes"],
                                   "algorithmic_bytes": 4 * 32768 * 1280 * 2,
-                                  "source": "profiles/cfg4_attention_hbm_traffic.txt"}
+                                  "source": "profiles/cfg4_hbm_traffic.txt"}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["avg_launch_us"] = round(avg_s * 1e6, 2)
     roof["launches_per_step"] = cnt_dom // steps
