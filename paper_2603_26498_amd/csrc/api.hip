@@ -88,6 +88,11 @@ int attn_bq_bf16(int dh, int heads, const std::vector<int64_t>& seg_len) {
   for (int64_t n : seg_len) { rows += n; padded += (n + 511) / 512 * 512; items256 += (n + 255) / 256; }
   // a single small request: fewer 256-row work items than CUs; 128-row items double the workgroups
   if (items256 * heads < 256) return 128;
+  // segments that fill their last 256-row item badly (576 tokens: 3 items for 2.25 items' worth of rows): 128-row
+  // items when they cut the padded rows by a tenth or more
+  int64_t p256 = 0, p128 = 0;
+  for (int64_t n : seg_len) { p256 += (n + 255) / 256 * 256; p128 += (n + 127) / 128 * 128; }
+  if (rows > 0 && p256 * 100 > rows * 115 && p128 * 100 <= p256 * 90) return 128;
   return (rows > 0 && padded * 100 <= rows * 103) ? 512 : 256;
 }
 
