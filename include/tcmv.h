@@ -5,8 +5,9 @@
  * Inference") splits a multimodal request into inference stages (Sec. 2.1,
  * Fig. 1): vision preprocessing, vision encoding, then the LLM.  Its Workload
  * Profiler (Sec. 3.2) times preprocessing and encoding separately, and its
- * characterisation (Sec. 2.2, Sec. 3.3 "TTFT breakdown") attributes the extra
- * latency of image and video requests to these two stages.  This library is
+ * characterisation (Sec. 2.2; the split of the time to first token in Sec. 3.3,
+ * Fig. 6) attributes the extra latency of image and video requests to these two
+ * stages.  This library is
  * those two stages plus the projection of visual tokens to the LLM width:
  *
  *     tcmv_preprocess     raw uint8 frames  -> normalised patch rows
