@@ -196,10 +196,11 @@ int tcmv_set_weights(tcmv_ctx *ctx, const tcmv_weights *w);
  * video length not a multiple of tpatch, src size < 1 for an item with frames,
  * a segment longer than max_pos rows (LEARNED_1D) or a grid side above max_pos
  * (SEPARABLE_2D), a grid side above 255, or so many tokens that tokens x widest
- * activation row (max of 3d, mlp, merge^2 d, k_pad) reaches 2^32, or the transposed
- * values (heads x head size rows of padded token columns; with attention windows
- * every window is padded to 64 columns) reach 2^32 elements (the kernels keep
- * element offsets in 32 bits; about 838 000 tokens at mlp = 5120).  Zero items,
+ * activation row (max of 3d, mlp, merge^2 d, k_pad) reaches 2^32, or tokens x 2 x
+ * attention width, or the transposed values (heads x head size rows of padded token
+ * columns; with attention windows every window is padded to 64 columns) reach 2^31
+ * elements (the kernels keep element offsets in 32 bits, the attention kernel byte
+ * offsets; about 838 000 tokens at d = 1280, mlp = 5120).  Zero items,
  * or only text items, give a valid empty plan.  Plans are immutable; the d_frames
  * pointers are recorded in the plan's metadata. */
 int tcmv_plan_create(tcmv_ctx *ctx, const tcmv_item *items, int n_items, tcmv_plan **out);

@@ -502,9 +502,12 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
     const int64_t widest = std::max<int64_t>({3LL * d.d, 3LL * attn_width_of(d), (int64_t)d.mlp, m2 * d.d, k_pad_of(d)});
     if ((double)(p->t_vpad + kVtAlign) * (double)widest >= 4294967296.0)
       return bad("too many tokens in one plan: tokens x widest activation row (max of 3d, mlp, merge^2 d, k_pad) must stay below 2^32");
-    // the transposed values: heads x head size rows of ldvt() columns (every window padded to 64 columns)
-    if ((double)(p->ldvt() + kVtAlign) * (double)attn_width_of(d) >= 4294967296.0)
-      return bad("too many tokens in one plan: the transposed values (padded columns x attention width) must stay below 2^32 elements");
+    // the attention kernel addresses its operands in bytes, 32 bits: the keys (rows of 2 x attention width) ...
+    if ((double)(p->t_vpad + kVtAlign) * 2.0 * (double)attn_width_of(d) >= 2147483648.0)
+      return bad("too many tokens in one plan: tokens x 2 x attention width must stay below 2^31 elements");
+    // ... and the transposed values: heads x head size rows of ldvt() columns (every window padded to 64 columns)
+    if ((double)(p->ldvt() + kVtAlign) * (double)attn_width_of(d) >= 2147483648.0)
+      return bad("too many tokens in one plan: the transposed values (padded columns x attention width) must stay below 2^31 elements");
   }
   p->n_segments = (int)seg_start.size();
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), d.heads, seg_len) : kAttnBQ_f32;
@@ -998,8 +1001,8 @@ int op_attention_check(int dtype, const void* d_qkv, const int64_t* cu_seqlens, 
   if (dtype == TCMV_BF16 ? !(dh == 32 || dh == 64 || dh == 80 || dh == 96) : (dh % 16 || dh > 128)) return TCMV_E_UNSUPPORTED;
   *L = op_attn_layout(dtype, cu_seqlens, n_seg, d, heads, nullptr, nullptr);
   if (L->T == 0) return TCMV_OK;
-  // the kernels keep element offsets into qkv and into the transposed values in 32 bits
-  if ((double)(L->t_vpad + kVtAlign) * 3.0 * (double)d >= 4294967296.0) return TCMV_E_UNSUPPORTED;
+  // the kernels keep byte offsets into qkv and into the transposed values in 32 bits
+  if ((double)(L->t_vpad + kVtAlign) * 3.0 * (double)d >= 2147483648.0) return TCMV_E_UNSUPPORTED;
   if (!d_qkv || !d_out || !d_index) return TCMV_E_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(d_index) % 256) return TCMV_E_INVALID_ARG;
   return TCMV_OK;

@@ -49,6 +49,17 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 }  // namespace
 
+// One wave-wide 16-byte-per-lane load global -> LDS through a buffer descriptor over `bytes` bytes at `base` (base,
+// size and `soff` are wave-uniform; `voff` is the lane's byte offset).  Lane l writes 16 bytes at lds + 16 l; bytes
+// past the end of the buffer read as zero.
+__device__ __forceinline__ void buffer_load_lds16(const void* base, uint32_t bytes, void* lds, uint32_t voff, uint32_t soff) {
+  const uint64_t v = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0,
+                                                                      (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)lds, 16, voff, soff, 0, 0);
+}
+
 template <int DH>
 struct AttnCfg {
   static constexpr int KS = DH / 16;                       // MFMA k-steps of the score product
@@ -160,7 +171,10 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   // lane fetches the global chunk that belongs at its LDS position: K rows are stored
   // with a padding chunk (odd chunk count per row), V^T chunks at their swizzled position.
   // The tile is C::NW wave-loads; wave w issues loads w, w+NWV, w+2*NWV, ...
-  uint32_t goff[NLD];             // element offset of this lane's tile-0 chunk from K (or VT)
+  // Both operands are addressed through buffer descriptors (base and size in SGPRs): a lane keeps one 32-bit byte
+  // offset per load, the tile index goes into the scalar offset, and rows past the end of the key buffer (last
+  // tile of the last segment) simply read as zero instead of being clamped - their scores are masked anyway.
+  uint32_t goff[NLD];             // byte offset of this lane's tile-0 chunk from K (or VT)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
@@ -173,24 +187,20 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     const int rowv = Lv >> 3, lc = (Lv & 7) ^ ((rowv >> 1) & 7);
     const uint32_t ko = (uint32_t)(head * DH) + (uint32_t)(w.seg_start + rowk) * (uint32_t)a.ldqk + cck * 8;
     const uint32_t vo = (uint32_t)(head * DH + rowv) * (uint32_t)a.ldv + (uint32_t)w.v0 + lc * 8;
-    goff[i] = (n < C::KROWCH) ? ko : vo;
+    goff[i] = ((n < C::KROWCH) ? ko : vo) * 2u;
   }
-  const uint32_t kstep = (uint32_t)BKV * (uint32_t)a.ldqk;
-  auto load_tile = [&](int t, int buf, bool tail) {
+  const uint32_t kstep = (uint32_t)BKV * (uint32_t)a.ldqk * 2u;
+  const uint32_t bytes_k = (uint32_t)(((uint64_t)(a.t_total - 1) * (uint64_t)a.ldqk + (uint64_t)a.heads * DH) * 2ull);
+  const uint32_t bytes_v = (uint32_t)((uint64_t)a.heads * DH * (uint64_t)a.ldv * 2ull);
+  auto load_tile = [&](int t, int buf, bool) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int n = wave_u + NWV * i;
       if (n < C::NW) {
         const bool is_k = n < C::KROWCH;
-        uint32_t off = goff[i] + (is_k ? (uint32_t)t * kstep : (uint32_t)t * BKV);
-        if (tail && is_k) {   // last tile: rows past the end of the buffer are clamped (their scores are masked)
-          const int rowk = (n * 64 + lane) / C::KROWCH;
-          const int64_t over = (int64_t)w.seg_start + t * BKV + rowk - (a.t_total - 1);
-          if (over > 0) off -= (uint32_t)over * (uint32_t)a.ldqk;
-        }
-        const uint16_t* src = (is_k ? K : VT) + off;
+        const uint32_t soff = is_k ? (uint32_t)t * kstep : (uint32_t)t * (BKV * 2);
         uint8_t* dst = smem + buf * C::STAGE + (is_k ? n * 1024 : C::K_BYTES + (n - C::KROWCH) * 1024);
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+        buffer_load_lds16(is_k ? (const void*)K : (const void*)VT, is_k ? bytes_k : bytes_v, dst, goff[i], soff);
       }
     }
   };
@@ -523,6 +533,8 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (total > (1 << 30)) return hipErrorInvalidValue;
   if (a.ldqk % 8 || a.ldv % 8 || a.ldo % 4) return hipErrorInvalidValue;
   if (a.bq != 128 && a.bq != 256 && a.bq != 512) return hipErrorInvalidValue;
+  // operands are addressed in bytes, 32 bits
+  if ((double)a.t_total * (double)a.ldqk * 2.0 >= 4294967296.0 || (double)a.heads * a.dh * (double)a.ldv * 2.0 >= 4294967296.0) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
   // with key norms both copies visit every work item and each item is processed by exactly one of them;
   // without, only the reference-tracking copy runs

@@ -217,4 +217,4 @@ def test_windowed_plan_whose_transposed_values_do_not_fit_32_bit_offsets_is_refu
     with pytest.raises(B.TcmvError) as e:
         enc.plan(items, upload=False)
     assert e.value.code == B.TCMV_E_BAD_SHAPE and "transposed" in str(e.value)
-    assert enc.plan(items[:1500], upload=False).info.n_tokens == 1500 * 64
+    assert enc.plan(items[:1000], upload=False).info.n_tokens == 1000 * 64
