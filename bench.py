@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_hbm_traffic.txt; both copies of the kernel).
 # Valid only for the kernel code it was taken with: reported as null once that file changes (comments aside).
-ATTN_TRAFFIC = {"source_sha256": "68dce7835300ddf2ac92702b49ae9438fe601a5837f8e6f8db99eb43d43b6e8c",
+ATTN_TRAFFIC = {"source_sha256": "bd224cf6fb2de76de393c15625f3578c3b307139dc13527ecc93d3d32a08b27f",
                 "workload": "cfg4_video64x448_vit32x1280_proj3584",
-                "fetch_bytes": 557308 * 1024, "write_bytes": 82672 * 1024}
+                "fetch_bytes": 557264 * 1024, "write_bytes": 82542 * 1024}
 
 
 def source_fingerprint(path):
