@@ -60,6 +60,14 @@ __device__ __forceinline__ void buffer_load_lds16(const void* base, uint32_t byt
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)lds, 16, voff, soff, 0, 0);
 }
 
+// One 16-byte-per-lane LDS read issued outside the compiler's view (inline assembly): the compiler neither moves it nor
+// waits for it; the caller places the s_waitcnt itself.  addr: LDS byte address of the lane, OFF: immediate offset.
+template <int OFF>
+__device__ __forceinline__ void lds_read16(bf16x8& dst, uint32_t addr, std::integral_constant<int, OFF>) {
+  static_assert(OFF >= 0 && OFF < 65536, "the offset field of an LDS read has 16 bits");
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+
 template <int DH>
 struct AttnCfg {
   static constexpr int KS = DH / 16;                       // MFMA k-steps of the score product
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   // ---- building blocks -------------------------------------------------------------
   // K fragments (A operand of the score MFMAs) of 32-key block kb of a staged tile; they are
   // requested one region before their use
-  bf16x8 kf[C::KS];
+  bf16x8 kf[C::KS > 6 ? C::KS : 6];      // K fragments; the pipelined region uses all six as a ring of fragments
   auto k_frags = [&](const uint8_t* sk, int kb) {
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks)
@@ -427,6 +435,108 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     }
   };
 
+  // The same region with the LDS fragment reads under explicit control (head size 80, two query tiles per wave).
+  // The 11 fragments of a region - 5 of K for the score MFMAs, 3 + 3 of V^T for the two halves of the PV product -
+  // form one stream through a ring of six registers: fragment g+5 is requested right after the MFMAs of fragment g
+  // have been issued (into the register of fragment g-1), so every read has about five fragments' worth of MFMAs
+  // (>= 300 cycles) to arrive.  Position 11 of a region is a gap (no read), which keeps the ring positions static.
+  // The reads are inline assembly: the compiler does not see them as LDS reads (left to itself it sinks every V^T read
+  // to just before its MFMA and waits there), so the waits are explicit too; LDS reads return in order, and nothing
+  // else in the loop uses that counter.  The vector work is placed by hand as well: two exponentials behind each of
+  // the first 16 MFMAs, their conversions one step later (no wait state after v_exp), scheduling fences in between.
+  // On entry kf[0..4] hold (or are about to receive) the K fragments of this region, on exit those of the next.
+  // Same arithmetic in the same order as region_fast: the results are bit-identical.
+  constexpr bool PIPE = FAST && DH == 80 && NT == 2;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+  const uint32_t koff = (uint32_t)(lr * C::KSTR + lg * 16);
+  uint32_t voff[2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) voff[kb][j] = (uint32_t)(lr * (BKV * 2) + (((4 * kb + 2 * j + lg) ^ ((lr >> 1) & 7)) << 4));
+  auto region_pipe = [&](f32x16 (&s_next)[NT], const f32x16 (&s_cur)[NT], uint32_t sv_addr, auto kbc, uint32_t sk_addr, auto kbp) {
+    if constexpr (PIPE) {
+    constexpr int kb_cur = decltype(kbc)::value, kb_pref = decltype(kbp)::value;
+    const uint32_t va[2] = {sv_addr + voff[kb_cur][0], sv_addr + voff[kb_cur][1]};
+    const uint32_t ka = sk_addr + koff;
+    float ex[4];                       // exponentials of the previous step, converted in this one
+    uint32_t pk[2][NT][4];             // packed probabilities: [half][query tile][4 x 2 bf16]
+    bf16x8 pf[2][NT];
+    static_for<11>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int slot = i % 6;
+      auto conv = [&]() {              // conversions of the exponentials of the previous step (no wait state after v_exp)
+        if constexpr (i >= 1 && i <= 8) {
+          constexpr int e0 = 4 * (i - 1);                 // exponentials e0 .. e0+3: half e/16, tile (e%16)/8, element e%8
+          constexpr int hj = e0 / 16, nt = (e0 % 16) / 8, q = (e0 % 8) / 2;
+          pk[hj][nt][q] = pack_bf16x2(ex[0], ex[1]);
+          pk[hj][nt][q + 1] = pack_bf16x2(ex[2], ex[3]);
+          if constexpr (q == 2) {
+            const uint4 u = make_uint4(pk[hj][nt][0], pk[hj][nt][1], pk[hj][nt][2], pk[hj][nt][3]);
+            pf[hj][nt] = __builtin_bit_cast(bf16x8, u);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      // one wait per three fragments (a wait costs an issue slot even when nothing is outstanding): before
+      // fragments i, i+1, i+2 are used, at most the two reads behind them may be outstanding (i+3 and i+4; position
+      // 11 is the gap, so behind 9 and 10 come the first two of the next region)
+      auto waitf = [&]() {
+        if constexpr (i % 3 == 0) {
+          if constexpr (i < 9)
+            asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[slot]), "+v"(kf[(i + 1) % 6]), "+v"(kf[(i + 2) % 6]));
+          else
+            asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[slot]), "+v"(kf[(i + 1) % 6]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      auto mfma = [&](auto ntc) {
+        constexpr int nt = decltype(ntc)::value;
+        if constexpr (i < 5) {
+          if constexpr (i == 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_next[nt][v] = 0.f;
+          }
+          s_next[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[slot], qf[nt][i], s_next[nt], 0, 0, 0);
+        } else {
+          constexpr int hj = (i - 5) / 3, mt = (i - 5) % 3;
+          o[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[slot], pf[hj][nt], o[mt][nt], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      auto exps = [&](auto ntc) {      // two exponentials behind each of the first 16 MFMAs
+        constexpr int nt = decltype(ntc)::value;
+        if constexpr (i < 8) {
+          constexpr int e0 = 4 * i + 2 * nt;
+          constexpr int hj = e0 / 16, ent = (e0 % 16) / 8, el = e0 % 8;
+          const float x0 = s_cur[ent][8 * hj + el], x1 = s_cur[ent][8 * hj + el + 1];
+          ex[2 * nt] = __builtin_amdgcn_exp2f(PRESC ? x0 : x0 * cs);
+          ex[2 * nt + 1] = __builtin_amdgcn_exp2f(PRESC ? x1 : x1 * cs);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      auto readf = [&]() {             // request fragment i+5 into the register of fragment i-1
+        constexpr int nslot = (i + 5) % 6;
+        if constexpr (i <= 2)
+          lds_read16(kf[nslot], va[0], std::integral_constant<int, i * 32 * BKV * 2>{});
+        else if constexpr (i <= 5)
+          lds_read16(kf[nslot], va[1], std::integral_constant<int, (i - 3) * 32 * BKV * 2>{});
+        else if constexpr (i >= 7)
+          lds_read16(kf[nslot], ka, std::integral_constant<int, kb_pref * 32 * C::KSTR + (i - 7) * 32>{});
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      constexpr std::integral_constant<int, 0> n0{};
+      constexpr std::integral_constant<int, 1> n1{};
+      // order inside a step (measured: requesting the next fragment between the second MFMA and its exponentials, and
+      // converting behind the first MFMA, is the fastest of ten orders tried; the spread is 3 %)
+      waitf(); mfma(n0); conv(); exps(n0); mfma(n1); readf(); exps(n1);
+    });
+    // position 11 is the gap; the fifth K fragment of the next region goes into ring position 16 % 6 = 4
+    lds_read16(kf[4], ka, std::integral_constant<int, kb_pref * 32 * C::KSTR + 4 * 32>{});
+    __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   // ---- pipeline ---------------------------------------------------------------------
   // LDS ring of three stages.  At the barrier that opens iteration t, tile t+1 has landed (its
   // loads were issued one iteration earlier) and every wave is done with tile t-1, so tile
@@ -460,7 +570,11 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     wait_tile();
     __syncthreads();
     if (t + 2 < n_tiles) load_tile(t + 2, st2, ragged && (t + 3 == n_tiles));
-    if constexpr (FAST) {
+    if constexpr (FAST && PIPE && !decltype(masked)::value) {
+      const uint32_t sva = lds0 + (uint32_t)(st * C::STAGE + C::K_BYTES), ska = lds0 + (uint32_t)(st1 * C::STAGE);
+      region_pipe(s1, s0, sva, std::integral_constant<int, 0>{}, ska, std::integral_constant<int, 0>{});
+      region_pipe(s0, s1, sva, std::integral_constant<int, 1>{}, ska, std::integral_constant<int, 1>{});
+    } else if constexpr (FAST) {
       region_fast(masked, s1, s0, sv, 0, sk1, 0, ragged && t + 1 == n_tiles, j0 + 32);
       region_fast(masked, s0, s1, sv, 1, sk1, 1, ragged && t + 2 == n_tiles, j0 + BKV);
     } else {
@@ -475,6 +589,9 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   // only the last two iterations can meet masked blocks (ragged tail) or the ignored extra block
   int t = 0;
   for (; t + 2 < n_tiles; ++t) iteration(std::false_type{}, t);
+  if constexpr (PIPE) {                // the ring's reads were issued outside the compiler's view: let them land
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]));
+  }
   for (; t < n_tiles; ++t) iteration(std::true_type{}, t);
 
   // ---- normalise and store: lane holds query (lane & 31), head-dim rows 8*(v/4) + 4*lg + v%4
