@@ -568,7 +568,12 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     const uint8_t* sv = smem + st * C::STAGE + C::K_BYTES;
     const uint8_t* sk1 = smem + st1 * C::STAGE;
     wait_tile();
-    __syncthreads();
+    // The barrier orders two things: every wave's tile loads have landed (the wait above) and every wave is done
+    // reading tile t-1 (each wave has waited for those fragments before it used them).  The pipelined regions keep
+    // LDS reads of tile t+1 in flight across it, so they take the bare barrier, not one that first drains the LDS
+    // counter.
+    if constexpr (FAST && PIPE && !decltype(masked)::value) __builtin_amdgcn_s_barrier();
+    else __syncthreads();
     if (t + 2 < n_tiles) load_tile(t + 2, st2, ragged && (t + 3 == n_tiles));
     if constexpr (FAST && PIPE && !decltype(masked)::value) {
       const uint32_t sva = lds0 + (uint32_t)(st * C::STAGE + C::K_BYTES), ska = lds0 + (uint32_t)(st1 * C::STAGE);
