@@ -593,6 +593,12 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   };
   // only the last two iterations can meet masked blocks (ragged tail) or the ignored extra block
   int t = 0;
+  if constexpr (PIPE) {
+    // The K fragments read above were the compiler's own loads: make it finish them here (it waits before the first
+    // use it sees), so that no wait of its own for them ends up inside the loop, where it would also wait for the
+    // ring's reads.
+    asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]));
+  }
   for (; t + 2 < n_tiles; ++t) iteration(std::false_type{}, t);
   if constexpr (PIPE) {                // the ring's reads were issued outside the compiler's view: let them land
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]));
