@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_hbm_traffic.txt; both copies of the kernel).
 # Valid only for the kernel code it was taken with: reported as null once that file changes (comments aside).
-ATTN_TRAFFIC = {"source_sha256": "13e9129e8e3a0dfbec24a6d3211359aa1126a495754237d85743331ca39b6655",
+ATTN_TRAFFIC = {"source_sha256": "c177418766c69e569ed0281e59a4dc83f1b455d071709433b1249a92edb24c20",
                 "workload": "cfg4_video64x448_vit32x1280_proj3584",
-                "fetch_bytes": 557357 * 1024, "write_bytes": 81948 * 1024}
+                "fetch_bytes": 557278 * 1024, "write_bytes": 82016 * 1024}
 
 
 def source_fingerprint(path):
