@@ -179,7 +179,7 @@ EncodeWs encode_ws(const tcmv_plan* p) {
   // (+ one word behind the table: "some workgroup needs the reference-tracking kernel").  Two such blocks: the
   // layers that use the table alternate between them, and the attention kernel of one layer clears the block
   // of the next.
-  w.kmax_bytes = align_up(((size_t)std::max(p->n_segments, p->n_windows) * d.heads + 1) * 4, 256);
+  w.kmax_bytes = align_up(((size_t)std::max(p->n_segments, p->n_windows) * d.heads + 1) * kKmaxStride * 4, 256);
   w.kmax = off; off += d.dtype == TCMV_BF16 ? 2 * w.kmax_bytes : 0;
   // one small request: room for the four k-slices of the fc2 product (see GemmArgs::partial)
   const bool few_rows = d.dtype == TCMV_BF16 && ((T + 127) / 128) * (((size_t)d.d + 127) / 128) < 200;
@@ -782,7 +782,7 @@ int tcmv_encode(tcmv_ctx* ctx, const tcmv_plan* p, const void* d_meta, const voi
             TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return launch_knorm(qk + da, 2 * da, T, d.heads, dh, row_seg, kmax, s); }),
                        "key norms");
           a.kmax2 = kmax;
-          a.any_left = kmax + (size_t)std::max(p->n_segments, p->n_windows) * d.heads;
+          a.any_left = kmax + (size_t)std::max(p->n_segments, p->n_windows) * d.heads * kKmaxStride;
           a.kmax_clear = kmax_other; a.n_clear = (int)(ws.kmax_bytes / 4);
         }
         TCMV_CHECK(timed(ctx, TCMV_K_ATTENTION, s, [&] { return short_windows ? launch_attn_window_bf16(a, s) : launch_attn_bf16(a, s); }),
@@ -938,7 +938,7 @@ OpAttnLayout op_attn_layout(int dtype, const int64_t* cu, int n_seg, int d, int 
   off = 0;
   L.vt = off;
   if (dtype == TCMV_BF16) off = align_up(off + (size_t)d * vp * 2, 256);
-  L.kmax_bytes = align_up((ss.size() * (size_t)heads + 1) * 4, 256);
+  L.kmax_bytes = align_up((ss.size() * (size_t)heads + 1) * kKmaxStride * 4, 256);
   L.kmax = off; off += L.kmax_bytes;
   L.ws_total = off;
   L.n_seg = ss.size();
@@ -982,7 +982,7 @@ int op_attention_run(int dtype, const void* d_qkv, int d, int heads, const OpAtt
     e = launch_knorm(q + d, 3 * d, L.T, heads, dh, reinterpret_cast<const int32_t*>(idx + L.rseg), kmax, s);
     if (e != hipSuccess) return TCMV_E_HIP;
     a.kmax2 = kmax;
-    a.any_left = kmax + L.n_seg * (size_t)heads;
+    a.any_left = kmax + L.n_seg * (size_t)heads * kKmaxStride;
     e = launch_attn_bf16(a, s);
   } else {
     const float* q = reinterpret_cast<const float*>(d_qkv);

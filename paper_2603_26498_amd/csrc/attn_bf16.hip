@@ -156,7 +156,7 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
   if (!a.kmax2) {            // no key norms: the caller wants every workgroup to take the reference-tracking copy
     if (FAST) return;
   } else {
-    const float kmax2 = __uint_as_float(a.kmax2[(size_t)w.seg * a.heads + head]);
+    const float kmax2 = __uint_as_float(a.kmax2[((size_t)w.seg * a.heads + head) * kKmaxStride]);
     const float c2 = PRESC ? 1.0f : a.scale * a.scale;
     bool ok = true;
 #pragma unroll
@@ -714,13 +714,13 @@ __global__ __launch_bounds__(256) void knorm_kernel(const uint16_t* k, int64_t l
     for (int r = 0; r < nr; ++r) {
       const int sg = row_seg[r0 + r];
       if (sg != seg) {
-        atomicMax(kmax2 + (size_t)seg * heads + h, __float_as_uint(mx));
+        atomicMax(kmax2 + ((size_t)seg * heads + h) * kKmaxStride, __float_as_uint(mx));
         seg = sg;
         mx = 0.f;
       }
       mx = fmaxf(mx, norm[r * heads + h]);
     }
-    atomicMax(kmax2 + (size_t)seg * heads + h, __float_as_uint(mx));
+    atomicMax(kmax2 + ((size_t)seg * heads + h) * kKmaxStride, __float_as_uint(mx));
   }
 }
 

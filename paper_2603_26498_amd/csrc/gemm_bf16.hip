@@ -286,9 +286,9 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
             vmax = fmaxf(vmax, lane_up8(vmax));
             const float top = fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 0)),
                                     __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 16)));
-            if (lane == 0) table_max(g.kmax2 + (size_t)seg_a * g.kn_heads + head0 + h, __float_as_uint(top));
+            if (lane == 0) table_max(g.kmax2 + ((size_t)seg_a * g.kn_heads + head0 + h) * kKmaxStride, __float_as_uint(top));
           } else if (row_ok && lg == 0) {
-            table_max(g.kmax2 + (size_t)seg * g.kn_heads + head0 + h, __float_as_uint(vmax));
+            table_max(g.kmax2 + ((size_t)seg * g.kn_heads + head0 + h) * kKmaxStride, __float_as_uint(vmax));
           }
         }
       }

@@ -7,6 +7,11 @@
 
 namespace tcmv {
 
+// Words between neighbouring entries of the key-norm table: every (segment, head) entry has a 128-byte line (and so an
+// L2 channel) to itself; thousands of waves check and raise these words while the QKV projection runs.
+constexpr int kKmaxStride = 32;
+
+
 // ---- device-visible descriptors (plain data, uploaded with a plan) ----------
 struct ItemDev {
   const uint8_t* frames;   // [n_frames, src_h, src_w, 3]
@@ -72,7 +77,7 @@ struct GemmArgs {
   int qcols; float qscale;
   // EPI_QKV, optional (see gemm_bf16_can_fuse_key_norms): kmax2[row_seg[r]][h] = max(.., 1.008 * |k row r, head h|^2)
   // over the key columns [qcols, split); kn_dh = head size, kn_heads = heads; float bits, table zeroed by the caller
-  uint32_t* kmax2; const int32_t* row_seg; int kn_dh; int kn_heads;
+  uint32_t* kmax2; const int32_t* row_seg; int kn_dh; int kn_heads;   // kmax2: one word per (segment, head), kKmaxStride words apart
   // EPI_RESID with few rows and a long contraction (one small request): when `partial` is given (fp32,
   // room for 4 * m * n values) the launcher may cut k into 4 slices computed by 4 times as many workgroups
   // and add the slices to C in slice order in a second kernel (same result from run to run)
