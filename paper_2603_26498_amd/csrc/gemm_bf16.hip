@@ -64,13 +64,6 @@ __device__ __forceinline__ float lane_xor2(float v) { return dpp_move<0x4E>(v); 
 __device__ __forceinline__ float lane_up4(float v) { return dpp_move<0x104>(v); }   // row_shl:4
 __device__ __forceinline__ float lane_up8(float v) { return dpp_move<0x108>(v); }   // row_shl:8
 
-// *p = max(*p, v).  Thousands of waves update the few words of one table: the atomic is only issued when the word, as
-// this wave sees it, is smaller (a stale view only costs an atomic that changes nothing), which leaves a handful of
-// atomics per word instead of one per wave queued behind each other.
-__device__ __forceinline__ void table_max(uint32_t* p, uint32_t v) {
-  if (__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < v) atomicMax(p, v);   // the load bypasses the CU's own cache
-}
-
 // Rows and columns of the output that a workgroup may write: [row_lo, row_hi) x [col_lo, col_hi).
 struct TileBounds { int64_t row_lo, row_hi; int col_lo, col_hi; int slice; };
 
@@ -274,6 +267,10 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
       const bool one_segment = __all(row_ok) && seg_a == seg_b;        // rows are ordered by segment
       const int head0 = (wcol0 - g.qcols) / g.kn_dh;
       const int nh = TN / g.kn_dh;
+      // all table words of the block are read before any is compared: one memory round trip per block, not one per head
+      uint32_t bits[4] = {0u, 0u, 0u, 0u}, seen[4] = {0u, 0u, 0u, 0u};
+      const bool writer = one_segment ? lane == 0 : (row_ok && lg == 0);
+      uint32_t* word = g.kmax2 + ((size_t)(one_segment ? seg_a : (row_ok ? seg : 0)) * g.kn_heads + head0) * kKmaxStride;
 #pragma unroll
       for (int h = 0; h < 4; ++h) {
         if (h < nh) {
@@ -284,14 +281,19 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
             vmax = fmaxf(vmax, lane_xor2(vmax));
             vmax = fmaxf(vmax, lane_up4(vmax));
             vmax = fmaxf(vmax, lane_up8(vmax));
-            const float top = fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 0)),
-                                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 16)));
-            if (lane == 0) table_max(g.kmax2 + ((size_t)seg_a * g.kn_heads + head0 + h) * kKmaxStride, __float_as_uint(top));
-          } else if (row_ok && lg == 0) {
-            table_max(g.kmax2 + ((size_t)seg * g.kn_heads + head0 + h) * kKmaxStride, __float_as_uint(vmax));
+            vmax = fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 0)),
+                         __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vmax), 16)));
           }
+          bits[h] = __float_as_uint(vmax);
+          if (writer) seen[h] = __hip_atomic_load(word + h * kKmaxStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
+      // *p = max(*p, v).  Thousands of waves update the few words of one table: the atomic is only issued when the
+      // word, as this wave has just seen it, is smaller (a stale view only costs an atomic that changes nothing),
+      // which leaves a handful of atomics per word instead of one per wave queued behind each other.
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+        if (h < nh && writer && seen[h] < bits[h]) atomicMax(word + h * kKmaxStride, bits[h]);
     }
   }
 }
