@@ -599,7 +599,10 @@ __global__ __launch_bounds__(NWV * 64, 8 / NWV) void attn_bf16_kernel(AttnArgs a
     // ring's reads.
     asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]));
   }
-  for (; t + 2 < n_tiles; ++t) iteration(std::false_type{}, t);
+  // A segment that fills its last tile needs no masks at all: its last two tiles run through the mask-free body
+  // too (the extra block that the last region scores comes from a stale stage, stays inside LDS and is ignored).
+  const int n_plain = (PIPE && !ragged) ? n_tiles : n_tiles - 2;
+  for (; t < n_plain; ++t) iteration(std::false_type{}, t);
   if constexpr (PIPE) {                // the ring's reads were issued outside the compiler's view: let them land
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]));
   }
