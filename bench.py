@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the attention kernel on the video workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (profiles/cfg4_hbm_traffic.txt; both copies of the kernel).
 # Valid only for the kernel code it was taken with: reported as null once that file changes (comments aside).
-ATTN_TRAFFIC = {"source_sha256": "35a5a811cdb6c08c8a2373b761cf1689a96aee207354da74eb55d7bf8dbe0f6d",
+ATTN_TRAFFIC = {"source_sha256": "23f9b0ede077e3e753627bf88f3d61622bd424b3a3e02d29cf12a04eaec7c4ea",
                 "workload": "cfg4_video64x448_vit32x1280_proj3584",
-                "fetch_bytes": 557294 * 1024, "write_bytes": 82006 * 1024}
+                "fetch_bytes": 557272 * 1024, "write_bytes": 82114 * 1024}
 
 
 def source_fingerprint(path):
