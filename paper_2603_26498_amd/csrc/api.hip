@@ -513,12 +513,14 @@ int tcmv_plan_create(tcmv_ctx* ctx, const tcmv_item* items, int n_items, tcmv_pl
   p->bq = d.dtype == TCMV_BF16 ? attn_bq_bf16(head_dim_of(d), d.heads, seg_len) : kAttnBQ_f32;
   build_work(p->work, seg_start, seg_len, seg_v0, p->bq);
   if (d.window) build_work(p->work_win, win_start, win_len, win_v0, kAttnBQ_window);
-  // The key-norm pass costs one read of K per layer; what it can save grows with the number of keys per query.
-  // It pays from about 2048 keys per query on average.
+  // The key norms come out of the QKV epilogue (a few table updates per tile) and the second attention launch costs a
+  // few microseconds; what the reference-free loop saves grows with the number of keys per query.  Measured: it pays
+  // from about 1024 keys per query on average (64 stills of 1024 tokens: attention 15.7 -> 12.9 ms per step) and
+  // costs time on batches of 577- or 729-token images, which run one query tile per wave.
   auto long_enough = [](const std::vector<int64_t>& len) {
     double rows = 0, pairs = 0;
     for (int64_t n : len) { rows += (double)n; pairs += (double)n * (double)n; }
-    return rows > 0 && pairs >= 2048.0 * rows;
+    return rows > 0 && pairs >= 1024.0 * rows;
   };
   p->norm_bound = d.dtype == TCMV_BF16 && long_enough(seg_len);
   p->norm_bound_win = d.dtype == TCMV_BF16 && long_enough(win_len);
