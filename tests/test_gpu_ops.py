@@ -173,6 +173,8 @@ def test_attention(lens, d, heads, qs, dtype):
     ([1000, 333, 1, 0, 640, 257, 129, 2048], 6.0, None),     # ragged: 256-row work items (4 waves x 2 query tiles), peaked
     ([2048, 2048, 1024], 6.0, None),                          # multiples of 512: 512-row work items (8 waves), peaked
     ([4096, 3072], 1.0, 3),                                   # long segments: key-norm bound holds except for one head
+    ([1000, 333, 2085, 640, 1500, 64], 1.0, None),            # small scores, ragged: the reference-free loop with masked last tiles
+    ([4096, 2560, 1536], 0.5, None),                          # small scores, full tiles, 512-row items: the reference-free loop without masks
 ])
 def test_attention_large_work_items(lens, qs, big_head):
     """Enough work items for the kernels with two query tiles per wave to be chosen (a single small problem
