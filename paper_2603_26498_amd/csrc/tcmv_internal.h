@@ -56,7 +56,8 @@ enum Epilogue {
   EPI_EMBED = 3,   // C(fp32)[dst_row[r]] = acc + bias + position term
   EPI_QKV = 4,     // columns < split: C ; columns >= split: transposed-V buffer
   EPI_GATED = 5,   // columns come in (gate, up) pairs: C[:, j] = silu(gate_j) * up_j   (C has n/2 columns)
-  EPI_PARTIAL = 6  // internal: raw fp32 sums of one slice of k into partial[slice][m][n] (see GemmArgs::partial)
+  EPI_PARTIAL = 6, // internal: raw fp32 sums of one slice of k into partial[slice][m][n] (see GemmArgs::partial)
+  EPI_RESID_AHEAD = 7  // internal: EPI_RESID for outputs too large to stay cached; old values requested one group ahead
 };
 
 struct GemmArgs {

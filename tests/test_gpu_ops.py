@@ -88,6 +88,26 @@ def test_gemm_bf16(m, n, k, epi):
         assert_tokens_close(got, ref, 1e-2, 0.9999, "gemm")
 
 
+@pytest.mark.parametrize("m,n,k", [(26000 + 37, 2560, 128), (66000, 1024, 64)])
+def test_residual_epilogue_on_an_output_larger_than_the_cache(m, n, k):
+    """fp32 outputs above 256 MB take the form of the residual epilogue that requests the old values one group of
+    columns ahead (both large tile families, ragged rows); every row is checked."""
+    rng = np.random.default_rng(m + n)
+    a = bf16_grid(rng.normal(0, 1, (m, k)))
+    w = bf16_grid(rng.normal(0, 0.05, (n, k)))
+    bias = rng.normal(0, 0.5, n).astype(np.float32)
+    c0 = rng.normal(0, 1, (m, n)).astype(np.float32)
+    assert m * n * 4 > 256e6
+    c = dev(c0)
+    B.tcmv_op_gemm(B.TCMV_BF16, B.EPI_RESID, dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), c, m, n, k)
+    sync()
+    got = c.cpu().numpy()
+    for lo in range(0, m, 8192):                      # reference in slabs: float64 of the whole output would be 0.5 GB
+        hi = min(m, lo + 8192)
+        ref = _gemm_ref(a[lo:hi], w, bias, B.EPI_RESID, c0[lo:hi])
+        assert np.abs(got[lo:hi] - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max()), (lo, hi)
+
+
 def test_gemm_bf16_no_bias_and_exact_small_integers():
     """Small integer inputs make every product and sum exact: bit-exact result expected."""
     rng = np.random.default_rng(0)
