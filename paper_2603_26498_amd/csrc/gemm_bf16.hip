@@ -241,7 +241,8 @@ __device__ __forceinline__ void wave_epilogue(f32x16 (&acc)[MI][NI], const GemmA
     // Outputs that do not stay cached between the kernels that update them (hundreds of megabytes of residual stream):
     // all groups of the wave tile in one sequence, the old values of group i+1 on their way while group i is written out.
     // It costs registers (two sets of old values; the compiler spills a few dozen), which is why outputs that do stay
-    // cached keep the plain form: measured 14 % faster on fc2 at 100 k tokens, 0.6 % slower at 32 k.
+    // cached keep the plain form: measured 14 % faster on fc2 at 100 k tokens (0.5 GB), 1 - 3 % slower at 32 k and 65 k
+    // tokens (0.17 and 0.34 GB), hence the launcher's threshold of 0.4 GB.
     constexpr int G = NI / 2 + (NI & 1);           // groups per 32-row block: pairs of 32-column tiles, then a single one
     float4 oa[4][2], ob[4][2];
     load_old(std::integral_constant<int, (NI >= 2 ? 2 : 1)>{}, 0, m_base, oa);
@@ -868,7 +869,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
       !(gk != GK_INVALID && (a.kn_dh == 64 || a.kn_dh == 80) && tn % a.kn_dh == 0 && a.qcols % tn == 0 &&
         a.split == 2 * a.qcols && a.row_seg && ((gk != GK_P320 && gk != GK_P256) || a.n % bn == 0)))
     return hipErrorInvalidValue;
-  if ((gk == GK_P320 || gk == GK_P256) && a.epi == EPI_RESID && (double)a.m * (double)a.n * 4.0 > 256e6) {
+  if ((gk == GK_P320 || gk == GK_P256) && a.epi == EPI_RESID && (double)a.m * (double)a.n * 4.0 > 400e6) {
     GemmArgs g = a;                                 // an output larger than the last-level cache: see wave_epilogue
     g.epi = EPI_RESID_AHEAD;
     return gk == GK_P320 ? launch_persist<256, 320, 4, 2>(g, s) : launch_persist<256, 256, 2, 4>(g, s);
